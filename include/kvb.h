@@ -1,0 +1,161 @@
+/*
+ * kvb -- KVBuffer-style Gated DeltaNet decoding for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  Every pointer marked "device" is device memory owned
+ * by the caller; the library never allocates, frees or synchronises, keeps no
+ * global state, and enqueues all work on the caller's HIP stream (`stream` is a
+ * hipStream_t passed as void*; NULL = the default stream).  The two structs are
+ * host memory and are read only during the call.
+ *
+ * Notation (paper Sec. 2.1, Sec. 3, App. A.1).  For one request and one v-head:
+ *   S0    the committed state, dk x dv, fp32                (the "state slot", Sec. 2.2)
+ *   f     number of records in the request's buffer         ("fill")
+ *   record l (0 <= l < f) = ( k_l, u_l, G_l ):
+ *         k_l  key of the l-th token since the last flush
+ *         u_l  its delta value (the quantity the paper buffers instead of v)
+ *         G_l  sum of the log decays g of tokens 0..l of the chunk, so that
+ *              gamma_l = exp(G_l) and Gamma_{il} = exp(G_i - G_l) <= 1 for i >= l
+ *   For a new token at chunk position i (App. A.1, Eq. 16):
+ *         u_i = beta_i ( v_i - gamma_i k_i S0 - sum_{l<i}  Gamma_{il} (k_i.k_l) u_l )
+ *         o_i = scale  ( gamma_i q_i S0       + sum_{l<=i} Gamma_{il} (q_i.k_l) u_l )
+ *         S   = gamma_m-1 S0 + sum_{l<m} Gamma_{m-1,l} k_l^T u_l          (flush of m records)
+ *   which is exactly the token-by-token recurrence of Eq. 11-12 regrouped.
+ *
+ * Grouped heads: v-head h uses the q and k of qk-head h / (Hv / Hk).
+ * The gate is passed as a log decay g <= 0 (alpha = exp(g)); gamma ratios are
+ * never formed, only exp of differences.
+ */
+#ifndef KVB_H
+#define KVB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVB_VERSION 100
+
+/* return codes */
+#define KVB_OK            0
+#define KVB_EINVAL       (-1) /* null / misaligned pointer, size out of range          */
+#define KVB_EUNSUPPORTED (-2) /* head size or dtype combination that is not compiled    */
+#define KVB_EHIP         (-3) /* the HIP runtime refused the launch                     */
+
+/* element types of q, k, v and of the buffered keys */
+#define KVB_F32  0
+#define KVB_BF16 1
+
+#define KVB_MAX_CAP        128 /* largest `cap` (the paper buffers at most d records, Sec. 3.4) */
+#define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
+#define KVB_MAX_DIRECT_LEN  64 /* largest Lmax of kvb_direct in this build                      */
+
+/* bit set in status[slot] when a call would have overrun that request's buffer */
+#define KVB_STATUS_OVERFLOW 1
+
+typedef struct kvb_shape {
+    int32_t B;         /* requests in this call (0 = no-op)                                */
+    int32_t Hk;        /* q/k heads                                                        */
+    int32_t Hv;        /* v heads, Hv % Hk == 0                                            */
+    int32_t dk;        /* key/query head size;   compiled: dk == dv in {32, 64, 128}       */
+    int32_t dv;        /* value head size                                                  */
+    int32_t cap;       /* records one request's buffer can hold, 1..KVB_MAX_CAP            */
+    int32_t in_dtype;  /* KVB_F32 or KVB_BF16: type of q, k, v and of buf_k                */
+    int32_t out_dtype; /* KVB_F32 only                                                     */
+    float   scale;     /* multiplies every output (1.0 = the paper's formulas)             */
+} kvb_shape;
+
+typedef struct kvb_store {
+    float   *state;   /* device [n_slots, Hv, dk, dv] fp32, dv contiguous.  May be NULL for
+                         kvb_decode / kvb_verify: KV-only mode, S0 taken as zero (Sec. 3.4). */
+    void    *buf_k;   /* device [n_slots, Hk, cap, dk] in_dtype                             */
+    float   *buf_u;   /* device [n_slots, Hv, cap, dv] fp32                                 */
+    float   *buf_G;   /* device [n_slots, Hv, cap]     fp32                                 */
+    int32_t *fill;    /* device [n_slots]; 0..cap between calls.  While a call that changes
+                         fill runs, bits 16.. of the word count the workgroups that have
+                         read it; the last one stores the new fill, so the word is a plain
+                         count again when the call's kernel ends.                           */
+    int32_t *status;  /* device [n_slots] sticky KVB_STATUS_* bits, or NULL                 */
+    int32_t  n_slots; /* slots in the arrays above; requests whose slot is outside
+                         0..n_slots-1 are skipped                                           */
+} kvb_store;
+
+/*
+ * All four calls take `slot`: device int32 [B], the store slot of request b.
+ * A slot must not appear twice in one call.  state, buf_k, buf_u, q, k, v and
+ * out must be 16-byte aligned; the int32 / float vectors 4-byte aligned.
+ */
+
+/*
+ * kvb_decode -- chunkwise decoding of ONE new token per request (Sec. 3.2; the
+ * single-token chunkwise form, App. A.1 Eq. 16; with store->state == NULL the
+ * single-token parallel form, Eq. 14).  Reads S0 and records 0..f-1, writes the
+ * output and record f = (k, u, G_f), then fill = f + 1.  Never writes `state`.
+ *   q, k  device [B, Hk, dk] in_dtype      v    device [B, Hv, dv] in_dtype
+ *   g     device [B, Hv] fp32 log decay    beta device [B, Hv] fp32
+ *   out   device [B, Hv, dv] fp32
+ * A request with f == cap is skipped: its out row and buffer are left as they
+ * are and status[slot] gets KVB_STATUS_OVERFLOW.
+ */
+int kvb_decode(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,
+               const void *q, const void *k, const void *v,
+               const float *g, const float *beta, void *out, void *stream);
+
+/*
+ * kvb_flush -- the deferred, batched state update (Sec. 3.2, Eq. 5; for GDN the
+ * last line of App. A.1 Eq. 16; with `accepted` the accepted-only update of
+ * Sec. 3.3 Eq. 8).  For request b: m = fill + (accepted ? accepted[b] : 0); if
+ * m >= threshold and m > 0:  S <- exp(G_{m-1}) S + sum_l exp(G_{m-1} - G_l) k_l^T u_l
+ * and fill = 0; otherwise fill = m and the state is untouched.  The only call
+ * that writes `state` (which must not be NULL).  On a zeroed state this is the
+ * KV-only -> state transition of Sec. 3.4.
+ *   accepted  device int32 [B] (each 0..T of the preceding kvb_verify) or NULL
+ *   threshold 1..cap; 1 flushes every non-empty buffer
+ * m > cap sets KVB_STATUS_OVERFLOW and is treated as cap.
+ */
+int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,
+              const int32_t *accepted, int32_t threshold, void *stream);
+
+/*
+ * kvb_verify -- parallel verification of T sequential draft tokens per request
+ * (Sec. 3.3, Eq. 7; for GDN the chunkwise matrix form App. A.1 Eq. 15 restricted
+ * to rows f..f+T-1).  One pass over S0 serves all T drafts; no temporary state
+ * is formed.  Writes T outputs and records f..f+T-1 but leaves `fill` (and
+ * `state`) untouched: committing is kvb_flush(accepted, ...).
+ *   T     1..KVB_MAX_DRAFTS
+ *   q, k  device [B, T, Hk, dk]   v device [B, T, Hv, dv]   g, beta device [B, T, Hv]
+ *   out   device [B, T, Hv, dv] fp32
+ * A request with f + T > cap is skipped with KVB_STATUS_OVERFLOW.
+ */
+int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
+               const void *q, const void *k, const void *v,
+               const float *g, const float *beta, void *out, void *stream);
+
+/*
+ * kvb_direct -- state-free computation of a whole short context from its keys
+ * and values (Sec. 3.4; the parallel form App. A.1 Eq. 13).  For request b the
+ * first len[b] tokens are processed from a zero state: outputs for every
+ * position, records 0..len[b]-1, fill = len[b] (whatever the buffer held before
+ * is discarded).  `state` is neither read nor written.  Decoding then continues
+ * with kvb_decode (state NULL), and kvb_flush on a zeroed state folds the
+ * records into a state once the context outgrows the buffer.
+ *   len   device int32 [B], 0..Lmax        Lmax 1..min(cap, KVB_MAX_DIRECT_LEN)
+ *   q, k  device [B, Lmax, Hk, dk]  v device [B, Lmax, Hv, dv]  g, beta device [B, Lmax, Hv]
+ *   out   device [B, Lmax, Hv, dv] fp32; rows >= len[b] are not written
+ * len[b] outside 0..Lmax is clamped to Lmax with KVB_STATUS_OVERFLOW.
+ */
+int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,
+               const int32_t *len, int32_t Lmax,
+               const void *q, const void *k, const void *v,
+               const float *g, const float *beta, void *out, void *stream);
+
+/* Static text for a return code (for KVB_EHIP: the last HIP error string of this thread). */
+const char *kvb_strerror(int code);
+
+/* KVB_VERSION of the built library. */
+int kvb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVB_H */

@@ -1,0 +1,150 @@
+"""ctypes binding of the kvb C ABI (include/kvb.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libkvb.so; nothing here
+computes.  PyTorch supplies device memory (``tensor.data_ptr()``) and the stream.
+The library must have been built (``python -m paper_2605_19049_amd.build``);
+there is no fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvb.so")
+
+OK, EINVAL, EUNSUPPORTED, EHIP = 0, -1, -2, -3
+F32, BF16 = 0, 1
+MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 64
+STATUS_OVERFLOW = 1
+
+EXPORTS = ("kvb_decode", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_strerror", "kvb_version")
+
+
+class KvbShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hk", ctypes.c_int32), ("Hv", ctypes.c_int32),
+                ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("cap", ctypes.c_int32),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class KvbStore(ctypes.Structure):
+    _fields_ = [("state", ctypes.c_void_p), ("buf_k", ctypes.c_void_p), ("buf_u", ctypes.c_void_p),
+                ("buf_G", ctypes.c_void_p), ("fill", ctypes.c_void_p), ("status", ctypes.c_void_p),
+                ("n_slots", ctypes.c_int32)]
+
+
+class KvbError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, strerror(code), code))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded libkvb.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libkvb.so is missing: build it with `python -m paper_2605_19049_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        sp, tp = ctypes.POINTER(KvbShape), ctypes.POINTER(KvbStore)
+        L.kvb_decode.argtypes = [sp, tp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.kvb_flush.argtypes = [sp, tp, vp, vp, i32, vp]
+        L.kvb_verify.argtypes = [sp, tp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.kvb_direct.argtypes = [sp, tp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        for name in ("kvb_decode", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_version"):
+            getattr(L, name).restype = ctypes.c_int
+        L.kvb_strerror.argtypes = [ctypes.c_int]
+        L.kvb_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """Device address of a torch tensor, or an int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def shape(B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, out_dtype=F32):
+    return KvbShape(B, Hk, Hv, dk, dv, cap, in_dtype, out_dtype, scale)
+
+
+def store(state, buf_k, buf_u, buf_G, fill, status, n_slots):
+    return KvbStore(_ptr(state), _ptr(buf_k), _ptr(buf_u), _ptr(buf_G), _ptr(fill), _ptr(status), n_slots)
+
+
+def strerror(code):
+    return lib().kvb_strerror(code).decode()
+
+
+def version():
+    return lib().kvb_version()
+
+
+def _check(rc, where, check):
+    if check and rc != OK:
+        raise KvbError(rc, where)
+    return rc
+
+
+def kvb_decode(sh, st, slot, q, k, v, g, beta, out, stream=None, check=True):
+    rc = lib().kvb_decode(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), _ptr(q), _ptr(k), _ptr(v),
+                          _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
+    return _check(rc, "kvb_decode", check)
+
+
+def kvb_flush(sh, st, slot, accepted, threshold, stream=None, check=True):
+    rc = lib().kvb_flush(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), _ptr(accepted), threshold,
+                         _stream(stream))
+    return _check(rc, "kvb_flush", check)
+
+
+def kvb_verify(sh, st, slot, T, q, k, v, g, beta, out, stream=None, check=True):
+    rc = lib().kvb_verify(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), T, _ptr(q), _ptr(k), _ptr(v),
+                          _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
+    return _check(rc, "kvb_verify", check)
+
+
+def kvb_direct(sh, st, slot, lens, Lmax, q, k, v, g, beta, out, stream=None, check=True):
+    rc = lib().kvb_direct(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), _ptr(lens), Lmax, _ptr(q),
+                          _ptr(k), _ptr(v), _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
+    return _check(rc, "kvb_direct", check)
+
+
+class DeviceStore:
+    """Caller-side holder of the device arrays of include/kvb.h's kvb_store, allocated
+    with PyTorch (memory plumbing only)."""
+
+    def __init__(self, n_slots, Hk, Hv, dk, dv, cap, in_dtype, device="cuda", with_state=True):
+        import torch
+        kd = torch.bfloat16 if in_dtype == BF16 else torch.float32
+        self.n_slots, self.Hk, self.Hv, self.dk, self.dv, self.cap = n_slots, Hk, Hv, dk, dv, cap
+        self.in_dtype = in_dtype
+        self.state = torch.zeros((n_slots, Hv, dk, dv), dtype=torch.float32, device=device) \
+            if with_state else None
+        self.buf_k = torch.zeros((n_slots, Hk, cap, dk), dtype=kd, device=device)
+        self.buf_u = torch.zeros((n_slots, Hv, cap, dv), dtype=torch.float32, device=device)
+        self.buf_G = torch.zeros((n_slots, Hv, cap), dtype=torch.float32, device=device)
+        self.fill = torch.zeros((n_slots,), dtype=torch.int32, device=device)
+        self.status = torch.zeros((n_slots,), dtype=torch.int32, device=device)
+
+    def c(self, with_state=True):
+        return store(self.state if with_state else None, self.buf_k, self.buf_u, self.buf_G, self.fill,
+                     self.status, self.n_slots)

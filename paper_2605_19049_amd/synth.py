@@ -19,10 +19,12 @@ def round_to_bf16(x):
     """Round float values to the nearest bfloat16 (ties to even); returns float32
     holding exactly representable values."""
     a = np.ascontiguousarray(x, dtype=np.float32)
-    bits = a.view(np.uint32).astype(np.uint64)
-    lsb = (bits >> 16) & 1
-    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
-    return (rounded & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(a.shape)
+    bits = a.view(np.uint32)
+    out = (bits >> np.uint32(16)) & np.uint32(1)       # finite inputs: no uint32 wrap-around
+    out += np.uint32(0x7FFF)
+    out += bits
+    out &= np.uint32(0xFFFF0000)
+    return out.view(np.float32).reshape(a.shape)
 
 
 def bf16_bits(x):

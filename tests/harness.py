@@ -1,0 +1,168 @@
+"""Shared driver of the GPU parity tests and the smoke check.
+
+It uploads seeded synthetic inputs, calls the C ABI (through the ctypes binding)
+the way a serving loop would, and returns what the GPU produced next to what
+the fp64 oracle says.  The oracle is only ever called from here (test side).
+"""
+import numpy as np
+import torch
+
+from oracle import gdn as oracle
+from paper_2605_19049_amd import kvb, synth
+
+DT = {"f32": kvb.F32, "bf16": kvb.BF16}
+TOL = {"f32": 1e-5, "bf16": 2e-3}   # max |err| / RMS(oracle), per input type
+
+
+def dev(x, in_dtype=None, device="cuda"):
+    """numpy -> device tensor.  Token tensors go over in the workload's input type;
+    the values are already representable in it, so the cast is exact."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(device)
+    if in_dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t
+
+
+def rel_err(got, want):
+    """max-abs error over RMS of the oracle values (the parity metric)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    rms = np.sqrt(np.mean(want ** 2))
+    return float(np.max(np.abs(got - want)) / max(rms, 1e-300))
+
+
+def prefix_state(rng, B, Hk, Hv, dk, dv, in_dtype, n_prefix):
+    """Initial committed state: a zero state advanced by the oracle over an n_prefix-token
+    synthetic prompt, rounded once to fp32.  Both sides start from that fp32 array."""
+    S = np.zeros((B, Hv, dk, dv))
+    if n_prefix > 0:
+        p = synth.token_stream(rng, B, n_prefix, Hk, Hv, dk, dv, in_dtype)
+        _, _, S, _ = oracle.gdn_sequence(S, p["q"], p["k"], p["v"], p["g"], p["beta"])
+    return S.astype(np.float32)
+
+
+class Layer:
+    """One GDN layer's device store plus the call wrappers."""
+
+    def __init__(self, B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, n_slots=None, slots=None,
+                 with_state=True, device="cuda"):
+        self.B, self.Hk, self.Hv, self.dk, self.dv, self.cap = B, Hk, Hv, dk, dv, cap
+        self.in_dtype, self.scale, self.device = in_dtype, scale, device
+        self.n_slots = n_slots if n_slots is not None else B
+        self.ds = kvb.DeviceStore(self.n_slots, Hk, Hv, dk, dv, cap, DT[in_dtype], device, with_state)
+        self.slots_np = np.arange(B, dtype=np.int32) if slots is None else np.asarray(slots, np.int32)
+        self.slot = dev(self.slots_np)
+        self.with_state = with_state
+
+    def shape(self, B=None):
+        return kvb.shape(self.B if B is None else B, self.Hk, self.Hv, self.dk, self.dv, self.cap,
+                         DT[self.in_dtype], self.scale)
+
+    def set_state(self, S_f32):
+        self.ds.state[self.slot.long()] = dev(S_f32)
+
+    def get_state(self):
+        return self.ds.state[self.slot.long()].cpu().numpy()
+
+    def fill(self):
+        return self.ds.fill[self.slot.long()].cpu().numpy()
+
+    def status(self):
+        return self.ds.status[self.slot.long()].cpu().numpy()
+
+    def decode(self, tok, out, slot=None, B=None, use_state=None):
+        st = self.ds.c(self.with_state if use_state is None else use_state)
+        kvb.kvb_decode(self.shape(B), st, self.slot if slot is None else slot,
+                       tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)
+
+    def flush(self, threshold, accepted=None, slot=None, B=None):
+        kvb.kvb_flush(self.shape(B), self.ds.c(True), self.slot if slot is None else slot, accepted, threshold)
+
+    def verify(self, T, tok, out, use_state=None):
+        st = self.ds.c(self.with_state if use_state is None else use_state)
+        kvb.kvb_verify(self.shape(), st, self.slot, T, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)
+
+    def direct(self, lens, Lmax, tok, out):
+        kvb.kvb_direct(self.shape(), self.ds.c(False), self.slot, lens, Lmax,
+                       tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)
+
+
+def upload_tokens(tok, in_dtype):
+    """dict of [B,T,...] numpy arrays -> dict of device tensors (q,k,v in in_dtype)."""
+    return {"q": dev(tok["q"], in_dtype), "k": dev(tok["k"], in_dtype), "v": dev(tok["v"], in_dtype),
+            "g": dev(tok["g"]), "beta": dev(tok["beta"])}
+
+
+def step_view(dtok, t):
+    """Token t of every request as contiguous [B,...] tensors."""
+    return {n: x[:, t].contiguous() for n, x in dtok.items()}
+
+
+def run_decode(layer, S0, tok, C, flush_every_step=True, final_flush=True):
+    """Chunkwise decoding of tok (T tokens per request) from committed state S0, flushing
+    when the buffer holds C records.  Returns GPU outputs [B,T,Hv,dv], the u records as
+    the GPU wrote them [B,T,Hv,dv], and the final state (after a last flush of everything)."""
+    B, T = tok["q"].shape[:2]
+    layer.set_state(S0)
+    dtok = upload_tokens(tok, layer.in_dtype)
+    out = torch.empty((B, T, layer.Hv, layer.dv), dtype=torch.float32, device=layer.device)
+    u_rec = torch.empty_like(out)
+    sl = layer.slot.long()
+    fills = []
+    for t in range(T):
+        f_before = int(layer.ds.fill[sl[0]].item())
+        o_t = torch.empty((B, layer.Hv, layer.dv), dtype=torch.float32, device=layer.device)
+        layer.decode(step_view(dtok, t), o_t)
+        out[:, t] = o_t
+        u_rec[:, t] = layer.ds.buf_u[sl, :, f_before]
+        if flush_every_step:
+            layer.flush(C)
+        fills.append(int(layer.ds.fill[sl[0]].item()))
+    if final_flush:
+        layer.flush(1)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), u_rec.cpu().numpy(), layer.get_state(), fills
+
+
+def run_smoke(verbose=False):
+    """One small pass through all four calls on cuda:0 against the oracle."""
+    assert torch.cuda.is_available(), "smoke needs a GPU"
+    rng = np.random.default_rng(0)
+    B, Hk, Hv, d, C = 3, 2, 4, 128, 4
+    res = {}
+    # decode + flush
+    S0 = prefix_state(rng, B, Hk, Hv, d, d, "bf16", 8)
+    tok = synth.token_stream(rng, B, 10, Hk, Hv, d, d, "bf16")
+    lay = Layer(B, Hk, Hv, d, d, cap=8, in_dtype="bf16")
+    o, u, S, _ = run_decode(lay, S0, tok, C)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    res["decode_out"] = rel_err(o, o_ref)
+    res["flush_state"] = rel_err(S, S_ref)
+    # verify (empty buffer after the final flush), commit 2 of 3 drafts
+    T = 3
+    vt = synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16")
+    dvt = upload_tokens(vt, "bf16")
+    vo = torch.empty((B, T, Hv, d), dtype=torch.float32, device="cuda")
+    lay.verify(T, dvt, vo)
+    acc = np.full(B, 2, np.int32)
+    lay.flush(1, accepted=dev(acc))
+    o_ref, _, S_acc = oracle.kvb_verify_expected(S_ref, vt["q"], vt["k"], vt["v"], vt["g"], vt["beta"], acc)
+    res["verify_out"] = rel_err(vo.cpu().numpy(), o_ref)
+    res["verify_state"] = rel_err(lay.get_state(), S_acc)
+    # direct
+    L = 6
+    dt_ = synth.token_stream(rng, B, L, Hk, Hv, d, d, "bf16")
+    lens = np.array([6, 1, 4], np.int32)
+    lay2 = Layer(B, Hk, Hv, d, d, cap=8, in_dtype="bf16", with_state=False)
+    do = torch.zeros((B, L, Hv, d), dtype=torch.float32, device="cuda")
+    lay2.direct(dev(lens), L, upload_tokens(dt_, "bf16"), do)
+    o_ref, _, _ = oracle.kvb_direct_expected(dt_["q"], dt_["k"], dt_["v"], dt_["g"], dt_["beta"], lens)
+    got = do.cpu().numpy()
+    mask = ~np.isnan(o_ref)
+    res["direct_out"] = rel_err(got[mask], o_ref[mask])
+    torch.cuda.synchronize()
+    if verbose:
+        print("smoke rel errors:", {k: "%.2e" % v for k, v in res.items()}, flush=True)
+    for name, e in res.items():
+        assert e < TOL["bf16"], (name, e)
+    return res

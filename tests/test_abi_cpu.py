@@ -1,0 +1,109 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_19049_amd import kvb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "kvb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvb_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert set(names) == set(kvb.EXPORTS)
+    L = kvb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_error_strings():
+    assert kvb.version() == 100
+    assert kvb.strerror(kvb.OK) == "ok"
+    assert "invalid" in kvb.strerror(kvb.EINVAL)
+    assert "unsupported" in kvb.strerror(kvb.EUNSUPPORTED)
+    assert "unknown" in kvb.strerror(-99)
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(kvb.KvbShape) == 9 * 4
+    assert kvb.KvbStore.n_slots.offset == 6 * 8
+
+
+A = 0x1000  # a fake, well-aligned "device address": validation must fail before it is used
+
+
+def _store(**kw):
+    d = dict(state=A, buf_k=A, buf_u=A, buf_G=A, fill=A, status=A, n_slots=4)
+    d.update(kw)
+    return kvb.store(**d)
+
+
+def _decode(sh, st, **kw):
+    d = dict(slot=A, q=A, k=A, v=A, g=A, beta=A, out=A)
+    d.update(kw)
+    return kvb.kvb_decode(sh, st, d["slot"], d["q"], d["k"], d["v"], d["g"], d["beta"], d["out"],
+                          stream=0, check=False)
+
+
+GOOD = dict(B=2, Hk=2, Hv=4, dk=128, dv=128, cap=16, in_dtype=kvb.BF16)
+
+
+@pytest.mark.parametrize("bad, code", [
+    (dict(B=-1), kvb.EINVAL), (dict(Hk=0), kvb.EINVAL), (dict(Hk=3), kvb.EINVAL),
+    (dict(cap=0), kvb.EINVAL), (dict(cap=129), kvb.EINVAL), (dict(dk=0), kvb.EINVAL),
+    (dict(dk=96, dv=96), kvb.EUNSUPPORTED), (dict(dk=128, dv=64), kvb.EUNSUPPORTED),
+    (dict(in_dtype=2), kvb.EUNSUPPORTED), (dict(out_dtype=1), kvb.EUNSUPPORTED),
+])
+def test_bad_shapes_are_rejected(bad, code):
+    sh = kvb.shape(**{**GOOD, **bad})
+    assert _decode(sh, _store()) == code
+
+
+def test_bad_pointers_are_rejected():
+    sh = kvb.shape(**GOOD)
+    assert _decode(sh, _store(buf_u=None)) == kvb.EINVAL
+    assert _decode(sh, _store(fill=None)) == kvb.EINVAL
+    assert _decode(sh, _store(n_slots=0)) == kvb.EINVAL
+    assert _decode(sh, _store(state=A + 4)) == kvb.EINVAL      # misaligned
+    assert _decode(sh, _store(), q=None) == kvb.EINVAL
+    assert _decode(sh, _store(), out=A + 8) == kvb.EINVAL
+    assert _decode(sh, _store(), slot=None) == kvb.EINVAL
+    assert _decode(sh, _store(), g=A + 2) == kvb.EINVAL
+
+
+def test_empty_batch_is_a_noop_everywhere():
+    sh = kvb.shape(**{**GOOD, "B": 0})
+    st = _store()
+    assert _decode(sh, st) == kvb.OK
+    assert kvb.kvb_flush(sh, st, A, None, 1, stream=0, check=False) == kvb.OK
+    assert kvb.kvb_verify(sh, st, A, 4, A, A, A, A, A, A, stream=0, check=False) == kvb.OK
+    assert kvb.kvb_direct(sh, st, A, A, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.OK
+
+
+def test_flush_verify_direct_argument_ranges():
+    sh = kvb.shape(**GOOD)
+    st = _store()
+    assert kvb.kvb_flush(sh, st, A, None, 0, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_flush(sh, st, A, None, 17, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_flush(sh, _store(state=None), A, None, 1, stream=0, check=False) == kvb.EINVAL
+    for T in (0, 9, 17):
+        assert kvb.kvb_verify(sh, st, A, T, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
+    for Lmax in (0, 17, 65):
+        assert kvb.kvb_direct(sh, st, A, A, Lmax, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_direct(sh, st, A, None, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
+
+
+def test_check_flag_raises():
+    sh = kvb.shape(**{**GOOD, "cap": 0})
+    with pytest.raises(kvb.KvbError) as e:
+        kvb.kvb_flush(sh, _store(), A, None, 1, stream=0)
+    assert e.value.code == kvb.EINVAL

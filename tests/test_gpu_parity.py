@@ -1,0 +1,387 @@
+"""GPU parity: every kvb call against the fp64 recurrence oracle, through the C ABI.
+
+Metric: max |gpu - oracle| / RMS(oracle) over all compared values; bound 1e-5 for the
+all-fp32 workload and 2e-3 for bf16 inputs with fp32 state.
+"""
+import numpy as np
+import pytest
+import torch
+
+import harness as H
+from harness import oracle
+from paper_2605_19049_amd import kvb, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def ragged_warmup(layer, fills, wtok):
+    """Bring request b's buffer to fills[b] records by decoding its first fills[b] warm-up
+    tokens; step j only carries the requests that still need a record (slot subsets)."""
+    dt = H.upload_tokens(wtok, layer.in_dtype)
+    for j in range(int(fills.max(initial=0))):
+        idx = np.nonzero(fills > j)[0]
+        ii = torch.from_numpy(idx).to(layer.device)
+        tok = {n: x[ii, j].contiguous() for n, x in dt.items()}
+        out = torch.empty((len(idx), layer.Hv, layer.dv), dtype=torch.float32, device=layer.device)
+        layer.decode(tok, out, slot=layer.slot[ii].contiguous(), B=len(idx))
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.fill(), fills)
+
+
+# --------------------------------------------------------------------------- decode + flush
+@pytest.mark.parametrize("C", [8, 1, 2, 4, 32])
+def test_tiny_fp32_decode_flush(C):
+    """Workload 1: all fp32, B=1, 2 heads, d=32, 64-token prefix, 32 steps; any chunk size
+    gives the same outputs (chunk-size invariance)."""
+    w = synth.WORKLOADS["tiny_fp32"]
+    rng = np.random.default_rng(w.seed)
+    S0 = H.prefix_state(rng, w.B, w.Hk, w.Hv, w.dk, w.dv, "f32", w.prefix)
+    tok = synth.token_stream(rng, w.B, w.steps, w.Hk, w.Hv, w.dk, w.dv, "f32")
+    lay = H.Layer(w.B, w.Hk, w.Hv, w.dk, w.dv, cap=C, in_dtype="f32")
+    o, u, S, fills = H.run_decode(lay, S0, tok, C)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("tiny_fp32 C=%d rel err out/u/state: %.2e %.2e %.2e" % ((C,) + e))
+    assert max(e) < H.TOL["f32"]
+    assert fills == [(t + 1) % C for t in range(w.steps)]
+    assert not lay.status().any()
+
+
+@pytest.mark.parametrize("d, in_dtype, B, Hk, Hv, C, steps", [
+    (128, "bf16", 5, 2, 4, 16, 40),
+    (128, "f32", 2, 1, 2, 16, 20),
+    (64, "bf16", 3, 2, 2, 8, 20),
+    (64, "f32", 2, 1, 1, 8, 12),
+    (32, "bf16", 3, 1, 3, 8, 20),
+    (128, "bf16", 2, 1, 1, 64, 70),
+    (128, "bf16", 2, 2, 4, 128, 130),
+])
+def test_decode_flush_shapes(d, in_dtype, B, Hk, Hv, C, steps):
+    rng = np.random.default_rng(100 + d + C)
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
+    tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, scale=d ** -0.5)
+    o, u, S, _ = H.run_decode(lay, S0, tok, C)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"],
+                                                     scale=d ** -0.5)
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("d=%d %s C=%d rel err out/u/state: %.2e %.2e %.2e" % ((d, in_dtype, C) + e))
+    assert max(e) < H.TOL[in_dtype]
+
+
+def test_qwen3next_decode_full():
+    """Workload 2 at full size: B=64, 16/32 heads, d=128, bf16, C=16, 256 steps."""
+    w = synth.WORKLOADS["qwen3next_decode"]
+    rng = np.random.default_rng(w.seed)
+    S0 = H.prefix_state(rng, w.B, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype, w.prefix)
+    tok = synth.token_stream(rng, w.B, w.steps, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype)
+    lay = H.Layer(w.B, w.Hk, w.Hv, w.dk, w.dv, cap=w.cap, in_dtype=w.in_dtype)
+    o, u, S, fills = H.run_decode(lay, S0, tok, w.C)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("qwen3next_decode rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    assert fills == [(t + 1) % w.C for t in range(w.steps)]
+
+
+# --------------------------------------------------------------------------- verify
+def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=False):
+    rng = np.random.default_rng(seed)
+    fill_hi = C - 1 if fill_hi is None else fill_hi
+    S0 = np.zeros((B, Hv, d, d), np.float32) if kv_only else H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
+    fills = synth.buffer_fills(rng, B, 0, fill_hi)
+    wtok = synth.token_stream(rng, B, max(1, fill_hi), Hk, Hv, d, d, in_dtype)
+    vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
+    acc = synth.accepted_lengths(rng, B, T)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype)
+    lay.set_state(S0)
+    ragged_warmup(lay, fills, wtok)
+    # oracle: true state after the warm-up tokens
+    _, _, S_true, _ = oracle.gdn_sequence(S0, wtok["q"], wtok["k"], wtok["v"], wtok["g"], wtok["beta"], lens=fills)
+    o_ref, u_ref, S_acc = oracle.kvb_verify_expected(S_true, vtok["q"], vtok["k"], vtok["v"], vtok["g"],
+                                                     vtok["beta"], acc)
+    state_before = lay.ds.state.clone()
+    out = torch.full((B, T, Hv, d), float("nan"), dtype=torch.float32, device="cuda")
+    lay.verify(T, H.upload_tokens(vtok, in_dtype), out, use_state=not kv_only)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.ds.state, state_before), "kvb_verify wrote the state"
+    assert np.array_equal(lay.fill(), fills), "kvb_verify changed fill"
+    e_out = H.rel_err(out.cpu().numpy(), o_ref)
+    # draft records sit at f..f+T-1
+    u_got = np.stack([lay.ds.buf_u[b, :, fills[b]:fills[b] + T].cpu().numpy() for b in range(B)])  # [B,Hv,T,d]
+    e_u = H.rel_err(u_got.transpose(0, 2, 1, 3), u_ref)
+    # commit accepted prefix; flush the requests that reached C; then fold everything
+    lay.flush(C, accepted=H.dev(acc))
+    torch.cuda.synchronize()
+    m = fills + acc
+    assert np.array_equal(lay.fill(), np.where(m >= C, 0, m))
+    lay.flush(1)
+    torch.cuda.synchronize()
+    e_S = H.rel_err(lay.get_state(), S_acc)
+    assert not lay.status().any()
+    return e_out, e_u, e_S
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 8])
+def test_verify_small(T):
+    e = _verify_case(B=6, Hk=2, Hv=4, d=128, C=16, cap=16 + T - 1, T=T, in_dtype="bf16", seed=30 + T)
+    say("verify T=%d rel err out/u/state: %.2e %.2e %.2e" % ((T,) + e))
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_verify_tiny_fp32_and_d64():
+    e = _verify_case(B=3, Hk=1, Hv=2, d=32, C=8, cap=12, T=4, in_dtype="f32", seed=41)
+    say("verify fp32 d=32 rel err: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["f32"]
+    e = _verify_case(B=3, Hk=2, Hv=2, d=64, C=8, cap=12, T=4, in_dtype="bf16", seed=42)
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_verify_long_buffer():
+    e = _verify_case(B=4, Hk=1, Hv=2, d=128, C=64, cap=72, T=8, in_dtype="bf16", seed=43)
+    say("verify C=64 T=8 rel err: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_spec_verify_full():
+    """Workload 3 at full size: B=128, fill ~U(0,15), 4 drafts, accepted ~U(0,4)."""
+    w = synth.WORKLOADS["spec_verify"]
+    e = _verify_case(w.B, w.Hk, w.Hv, w.dk, w.C, w.cap, w.T, w.in_dtype, w.seed)
+    say("spec_verify rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+
+
+# --------------------------------------------------------------------------- direct
+def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True):
+    rng = np.random.default_rng(seed)
+    if lens is None:
+        lens = synth.context_lengths(rng, B, 1, Lmax)
+    tok = synth.token_stream(rng, B, Lmax, Hk, Hv, d, d, in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False)
+    lay.ds.fill.fill_(3)          # stale fill must be discarded
+    out = torch.full((B, Lmax, Hv, d), float("nan"), dtype=torch.float32, device="cuda")
+    lay.direct(H.dev(lens), Lmax, H.upload_tokens(tok, in_dtype), out)
+    torch.cuda.synchronize()
+    o_ref, u_ref, S_ref = oracle.kvb_direct_expected(tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], lens)
+    got = out.cpu().numpy()
+    valid = ~np.isnan(o_ref)
+    assert np.all(np.isnan(got[~valid])), "rows >= len were written"
+    e_out = H.rel_err(got[valid], o_ref[valid])
+    u_got = lay.ds.buf_u[:, :, :Lmax].cpu().numpy().transpose(0, 2, 1, 3)
+    e_u = H.rel_err(u_got[valid], u_ref[valid])
+    assert np.array_equal(lay.fill(), lens)
+    e_dec = 0.0
+    if then_decode:
+        # one KV-only decode step for the requests that still have room, then fold into a zero state
+        room = np.nonzero(lens < cap)[0]
+        nt = synth.token_stream(rng, B, 1, Hk, Hv, d, d, in_dtype)
+        ii = torch.from_numpy(room).cuda()
+        dt = H.upload_tokens(nt, in_dtype)
+        o1 = torch.empty((len(room), Hv, d), dtype=torch.float32, device="cuda")
+        lay.decode({n: x[ii, 0].contiguous() for n, x in dt.items()}, o1, slot=lay.slot[ii].contiguous(),
+                   B=len(room), use_state=False)
+        o1_ref, _, S_ref = oracle.gdn_sequence(S_ref, nt["q"], nt["k"], nt["v"], nt["g"], nt["beta"],
+                                               lens=(lens < cap).astype(np.int32))[:3]
+        e_dec = H.rel_err(o1.cpu().numpy(), o1_ref[room, 0])
+    lay.ds.state = torch.zeros((B, Hv, d, d), dtype=torch.float32, device="cuda")
+    lay.flush(1)
+    torch.cuda.synchronize()
+    e_S = H.rel_err(lay.get_state(), S_ref)
+    assert not lay.fill().any()
+    return e_out, e_u, e_dec, e_S
+
+
+@pytest.mark.parametrize("d, in_dtype, Lmax", [(128, "bf16", 64), (128, "bf16", 7), (32, "f32", 16),
+                                               (64, "bf16", 33), (128, "f32", 20)])
+def test_direct_small(d, in_dtype, Lmax):
+    e = _direct_case(B=5, Hk=2, Hv=4, d=d, Lmax=Lmax, cap=max(Lmax, 8), in_dtype=in_dtype, seed=50 + Lmax)
+    say("direct d=%d %s Lmax=%d rel err out/u/decode/state: %.2e %.2e %.2e %.2e" % ((d, in_dtype, Lmax) + e))
+    assert max(e) < H.TOL[in_dtype]
+
+
+def test_direct_len_zero_and_one():
+    e = _direct_case(B=4, Hk=1, Hv=2, d=128, Lmax=8, cap=8, in_dtype="bf16", seed=60,
+                     lens=np.array([0, 1, 8, 2], np.int32))
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_short_direct_full():
+    """Workload 4 at full size: B=256, context ~U(1,64), then one KV-only decode step."""
+    w = synth.WORKLOADS["short_direct"]
+    e = _direct_case(w.B, w.Hk, w.Hv, w.dk, w.Lmax, w.cap + 1, w.in_dtype, w.seed)
+    say("short_direct rel err out/u/decode/state: %.2e %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+
+
+# --------------------------------------------------------------------------- mixed batches
+def test_mixed_fill_batch_reduced():
+    """Workload 5 reduced (B=24, 2 layers, C=64): every request starts at its own fill, so a few
+    requests flush at each step; the flush call runs every step with a device-side predicate."""
+    B, Hk, Hv, d, C, steps, layers = 24, 2, 4, 128, 64, 80, 2
+    rng = np.random.default_rng(5)
+    for layer_i in range(layers):
+        S0 = H.prefix_state(rng, B, Hk, Hv, d, d, "bf16", 8)
+        fills = synth.buffer_fills(rng, B, 0, C - 1)
+        wtok = synth.token_stream(rng, B, C - 1, Hk, Hv, d, d, "bf16")
+        tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, "bf16")
+        lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+        lay.set_state(S0)
+        ragged_warmup(lay, fills, wtok)
+        _, _, S_true, _ = oracle.gdn_sequence(S0, wtok["q"], wtok["k"], wtok["v"], wtok["g"], wtok["beta"],
+                                              lens=fills)
+        dt = H.upload_tokens(tok, "bf16")
+        out = torch.empty((B, steps, Hv, d), dtype=torch.float32, device="cuda")
+        for t in range(steps):
+            o_t = torch.empty((B, Hv, d), dtype=torch.float32, device="cuda")
+            lay.decode(H.step_view(dt, t), o_t)
+            lay.flush(C)
+            out[:, t] = o_t
+        torch.cuda.synchronize()
+        assert np.array_equal(lay.fill(), (fills + steps) % C)
+        lay.flush(1)
+        o_ref, _, S_ref = oracle.kvb_decode_expected(S_true, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+        e = (H.rel_err(out.cpu().numpy(), o_ref), H.rel_err(lay.get_state(), S_ref))
+        say("mixed layer %d rel err out/state: %.2e %.2e" % ((layer_i,) + e))
+        assert max(e) < H.TOL["bf16"]
+        assert not lay.status().any()
+
+
+# --------------------------------------------------------------------------- edge cases
+def _small_layer(in_dtype="bf16", B=3, Hk=1, Hv=2, d=128, cap=4, **kw):
+    return H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, **kw)
+
+
+def test_decode_and_verify_never_write_state_and_overflow_is_flagged():
+    rng = np.random.default_rng(70)
+    lay = _small_layer()
+    S0 = synth.random_state(rng, 3, 2, 128, 128)
+    lay.set_state(S0)
+    tok = H.upload_tokens(synth.token_stream(rng, 3, 6, 1, 2, 128, 128, "bf16"), "bf16")
+    before = lay.ds.state.clone()
+    out = torch.full((3, 2, 128), 7.0, dtype=torch.float32, device="cuda")
+    for t in range(4):
+        lay.decode(H.step_view(tok, t), out)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.ds.state, before)
+    assert np.array_equal(lay.fill(), [4, 4, 4]) and not lay.status().any()
+    # buffer full: the 5th token is refused, nothing is written
+    u_before, out[:] = lay.ds.buf_u.clone(), 7.0
+    lay.decode(H.step_view(tok, 4), out)
+    vout = torch.full((3, 2, 2, 128), 7.0, dtype=torch.float32, device="cuda")
+    lay.verify(2, {n: x[:, :2].contiguous() for n, x in tok.items()}, vout)
+    torch.cuda.synchronize()
+    assert np.array_equal(lay.fill(), [4, 4, 4])
+    assert np.array_equal(lay.status(), [kvb.STATUS_OVERFLOW] * 3)
+    assert torch.equal(lay.ds.buf_u, u_before) and torch.all(out == 7.0) and torch.all(vout == 7.0)
+    assert torch.equal(lay.ds.state, before)
+
+
+def test_slot_indirection_leaves_other_slots_alone():
+    """Requests live in scattered slots of a larger store; unused slots hold poison that must
+    survive; a slot index outside the store is skipped."""
+    rng = np.random.default_rng(71)
+    B, n_slots = 3, 7
+    slots = np.array([5, 0, 3], np.int32)
+    lay = H.Layer(B, 1, 2, 128, 128, cap=4, in_dtype="bf16", n_slots=n_slots, slots=slots)
+    lay.ds.state.fill_(123.0)
+    lay.ds.buf_u.fill_(-55.0)
+    lay.ds.fill.fill_(2)
+    lay.ds.fill[lay.slot.long()] = 0
+    S0 = synth.random_state(rng, B, 2, 128, 128)
+    tok = synth.token_stream(rng, B, 6, 1, 2, 128, 128, "bf16")
+    o, u, S, _ = H.run_decode(lay, S0, tok, 4)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    assert max(H.rel_err(o, o_ref), H.rel_err(S, S_ref)) < H.TOL["bf16"]
+    others = torch.tensor([1, 2, 4, 6], device="cuda")
+    assert torch.all(lay.ds.state[others] == 123.0) and torch.all(lay.ds.buf_u[others] == -55.0)
+    assert torch.all(lay.ds.fill[others] == 2)
+    # out-of-range slots: the call succeeds and touches nothing
+    bad = H.dev(np.array([7, -1, 100], np.int32))
+    snap = (lay.ds.state.clone(), lay.ds.buf_u.clone(), lay.ds.fill.clone())
+    out = torch.full((B, 2, 128), 9.0, dtype=torch.float32, device="cuda")
+    lay.decode(H.step_view(H.upload_tokens(tok, "bf16"), 0), out, slot=bad)
+    lay.flush(1, slot=bad)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.ds.state, snap[0]) and torch.equal(lay.ds.buf_u, snap[1])
+    assert torch.equal(lay.ds.fill, snap[2]) and torch.all(out == 9.0)
+
+
+def test_closed_forms_on_the_gpu():
+    """beta = 0: outputs are prod(alpha) q S0 and flushing scales the state by prod(alpha);
+    beta = 0 and g = 0: flushing leaves the state bit-identical."""
+    rng = np.random.default_rng(72)
+    B, Hv, d = 2, 2, 128
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    tok = synth.token_stream(rng, B, 4, 1, Hv, d, d, "bf16")
+    tok["beta"][:] = 0
+    lay = _small_layer(B=B)
+    o, u, S, _ = H.run_decode(lay, S0, tok, 4, flush_every_step=False)
+    gam = np.exp(np.cumsum(tok["g"].astype(np.float64), axis=1))
+    want = gam[..., None] * np.einsum("bti,bhij->bthj", tok["q"][:, :, 0].astype(np.float64), S0.astype(np.float64))
+    assert H.rel_err(o, want) < 1e-5 and not u.any()
+    assert H.rel_err(S, gam[:, -1, :, None, None] * S0) < 1e-6
+    tok["g"][:] = 0
+    lay = _small_layer(B=B)
+    o, u, S, _ = H.run_decode(lay, S0, tok, 4, flush_every_step=False)
+    assert np.array_equal(S, S0)
+
+
+def test_strong_decay_neither_overflows_nor_underflows_to_nan():
+    """g = -20 per token over a 64-record chunk: gamma ratios are never formed."""
+    rng = np.random.default_rng(73)
+    B, Hk, Hv, d, C = 2, 1, 2, 128, 64
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    tok = synth.token_stream(rng, B, C + 3, Hk, Hv, d, d, "bf16")
+    tok["g"][:] = -20.0
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+    o, u, S, _ = H.run_decode(lay, S0, tok, C)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    assert np.isfinite(o).all() and np.isfinite(S).all()
+    assert max(H.rel_err(o, o_ref), H.rel_err(S, S_ref)) < H.TOL["bf16"]
+
+
+def test_accepting_nothing_appends_nothing():
+    rng = np.random.default_rng(74)
+    lay = _small_layer(cap=8)
+    S0 = synth.random_state(rng, 3, 2, 128, 128)
+    lay.set_state(S0)
+    vt = H.upload_tokens(synth.token_stream(rng, 3, 4, 1, 2, 128, 128, "bf16"), "bf16")
+    out = torch.empty((3, 4, 2, 128), dtype=torch.float32, device="cuda")
+    lay.verify(4, vt, out)
+    lay.flush(1, accepted=H.dev(np.zeros(3, np.int32)))
+    torch.cuda.synchronize()
+    assert not lay.fill().any()
+    assert np.array_equal(lay.get_state(), S0)
+
+
+def test_snapshot_restore_mid_chunk():
+    """State, buffer and fill are plain caller-owned arrays: copying them is a checkpoint."""
+    rng = np.random.default_rng(75)
+    B, Hk, Hv, d, C = 2, 1, 2, 128, 8
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    tok = synth.token_stream(rng, B, 12, Hk, Hv, d, d, "bf16")
+    dt = H.upload_tokens(tok, "bf16")
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+    lay.set_state(S0)
+    out = torch.empty((B, 12, Hv, d), dtype=torch.float32, device="cuda")
+
+    def steps(lo, hi, dst):
+        for t in range(lo, hi):
+            o_t = torch.empty((B, Hv, d), dtype=torch.float32, device="cuda")
+            lay.decode(H.step_view(dt, t), o_t)
+            lay.flush(C)
+            dst[:, t] = o_t
+
+    steps(0, 5, out)
+    snap = [x.clone() for x in (lay.ds.state, lay.ds.buf_k, lay.ds.buf_u, lay.ds.buf_G, lay.ds.fill)]
+    steps(5, 12, out)
+    for dst, src in zip((lay.ds.state, lay.ds.buf_k, lay.ds.buf_u, lay.ds.buf_G, lay.ds.fill), snap):
+        dst.copy_(src)
+    out2 = out.clone()
+    steps(5, 12, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
