@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVBuffer GDN decode path on one MI355X.
+
+One "step" = one chunkwise decoding step of the whole batch through one GDN layer:
+kvb_decode followed by kvb_flush(threshold = C) (the flush call is issued every step; its
+device-side predicate makes it a no-op until the buffer holds C records).  The headline
+workload is the Qwen3-Next-shaped layer: batch 64, 16 qk + 32 v heads, d = 128, bf16
+q/k/v, fp32 state, C = 16.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="qwen3next_decode")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
+                    help="graph: the K timed steps are one HIP graph launch; eager: one launch per kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-paths", action="store_true")
+    return ap.parse_args()
+
+
+class DecodeJob:
+    """Device-resident workload: store, a ring of token inputs, pre-marshalled calls."""
+
+    def __init__(self, w, ring=64):
+        import numpy as np
+        import torch
+        from paper_2605_19049_amd import kvb, synth
+        self.w, self.torch, self.kvb = w, torch, kvb
+        dt = kvb.BF16 if w.in_dtype == "bf16" else kvb.F32
+        self.ds = kvb.DeviceStore(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt)
+        self.sh = kvb.shape(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt, 1.0)
+        self.st = self.ds.c()
+        self.slot = torch.arange(w.B, dtype=torch.int32, device="cuda")
+        rng = np.random.default_rng(w.seed)
+        tok = synth.token_stream(rng, w.B, ring, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype)
+        tdt = torch.bfloat16 if w.in_dtype == "bf16" else torch.float32
+        self.ring = ring
+        self.tok_np = tok
+        self.tok = []
+        for t in range(ring):
+            self.tok.append({
+                "q": torch.from_numpy(tok["q"][:, t].copy()).cuda().to(tdt),
+                "k": torch.from_numpy(tok["k"][:, t].copy()).cuda().to(tdt),
+                "v": torch.from_numpy(tok["v"][:, t].copy()).cuda().to(tdt),
+                "g": torch.from_numpy(tok["g"][:, t].copy()).cuda(),
+                "beta": torch.from_numpy(tok["beta"][:, t].copy()).cuda()})
+        self.out = torch.empty((w.B, w.Hv, w.dv), dtype=torch.float32, device="cuda")
+        self.t = 0          # tokens decoded so far (selects the ring entry)
+        self._bound = {}
+
+    def _calls(self, stream):
+        key = stream
+        if key not in self._bound:
+            kvb = self.kvb
+            dec = [kvb.bind("kvb_decode", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
+                            x["beta"], self.out, stream) for x in self.tok]
+            fl = kvb.bind("kvb_flush", self.sh, self.st, self.slot, None, self.w.C, stream)
+            self._bound[key] = (dec, fl)
+        return self._bound[key]
+
+    def run(self, n, events=None):
+        """n steps on the current stream; with `events`, bracket every decode launch."""
+        torch = self.torch
+        dec, fl = self._calls(torch.cuda.current_stream().cuda_stream)
+        for _ in range(n):
+            d = dec[self.t % self.ring]
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                d()
+                e1.record()
+                events.append((e0, e1, self.t % self.w.C))
+            else:
+                d()
+            fl()
+            self.t += 1
+
+
+def time_other_paths(torch, kvb, synth, traffic, reps=20):
+    """Kernel-level timings of kvb_verify, kvb_direct and a 64-record kvb_flush at the
+    sizes of the spec_verify / short_direct / long_mixed workloads (context numbers only)."""
+    import numpy as np
+    res = {}
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    def dev_tok(tok):
+        return {n: (torch.from_numpy(x).cuda().to(torch.bfloat16) if n in "qkv" else torch.from_numpy(x).cuda())
+                for n, x in tok.items()}
+
+    # verify: B=128, fill ~U(0,15), T=4
+    w = synth.WORKLOADS["spec_verify"]
+    rng = np.random.default_rng(w.seed)
+    ds = kvb.DeviceStore(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, kvb.BF16)
+    ds.state.normal_(0, 0.5)
+    ds.buf_u.normal_(0, 1.0)
+    ds.buf_k.copy_(torch.nn.functional.normalize(torch.randn_like(ds.buf_k, dtype=torch.float32), dim=-1))
+    ds.buf_G.copy_(-0.25 * torch.arange(1, w.cap + 1, device="cuda").float().expand_as(ds.buf_G))
+    fills = synth.buffer_fills(rng, w.B, 0, w.C - 1)
+    ds.fill.copy_(torch.from_numpy(fills))
+    sh = kvb.shape(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, kvb.BF16)
+    st = ds.c()
+    slot = torch.arange(w.B, dtype=torch.int32, device="cuda")
+    tok = dev_tok(synth.token_stream(rng, w.B, w.T, w.Hk, w.Hv, w.dk, w.dv, "bf16"))
+    out = torch.empty((w.B, w.T, w.Hv, w.dv), dtype=torch.float32, device="cuda")
+    call = kvb.bind("kvb_verify", sh, st, slot, w.T, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out,
+                    torch.cuda.current_stream().cuda_stream)
+    sec = timed(call, reps)
+    byt = sum(traffic.total(traffic.verify_rw(traffic.KVB, int(f), w.T)) for f in fills) * w.Hv
+    res["kvb_verify"] = {"workload": "spec_verify B=128 T=4 fill~U(0,15)", "us": sec * 1e6,
+                         "algorithmic_GBps": byt / sec / 1e9, "draft_tokens_per_s": w.B * w.T / sec}
+    del ds
+
+    # direct: B=256, L ~U(1,64)
+    w = synth.WORKLOADS["short_direct"]
+    rng = np.random.default_rng(w.seed)
+    ds = kvb.DeviceStore(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, kvb.BF16, with_state=False)
+    lens = synth.context_lengths(rng, w.B, 1, w.Lmax)
+    dl = torch.from_numpy(lens).cuda()
+    sh = kvb.shape(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, kvb.BF16)
+    st = ds.c(False)
+    slot = torch.arange(w.B, dtype=torch.int32, device="cuda")
+    tok = dev_tok(synth.token_stream(rng, w.B, w.Lmax, w.Hk, w.Hv, w.dk, w.dv, "bf16"))
+    out = torch.empty((w.B, w.Lmax, w.Hv, w.dv), dtype=torch.float32, device="cuda")
+    call = kvb.bind("kvb_direct", sh, st, slot, dl, w.Lmax, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"],
+                    out, torch.cuda.current_stream().cuda_stream)
+    sec = timed(call, reps)
+    byt = sum(traffic.total(traffic.direct_rw(traffic.KVB, int(L))) for L in lens) * w.Hv
+    flop = sum(4.0 * int(L) ** 2 * w.dk for L in lens) * w.Hv
+    res["kvb_direct"] = {"workload": "short_direct B=256 L~U(1,64)", "us": sec * 1e6,
+                         "algorithmic_GBps": byt / sec / 1e9, "TFLOPs": flop / sec / 1e12,
+                         "context_tokens_per_s": float(lens.sum()) / sec}
+    del ds
+    return res
+
+
+def cpu_baseline(w, tok_np, steps=512):
+    """The fp64 oracle, as it stands, on the host cores: same shapes, same token values."""
+    import numpy as np
+    from oracle import gdn
+    gdn.build_lib()
+    ring = tok_np["q"].shape[1]
+    n = steps - steps % ring
+    S0 = np.zeros((w.B, w.Hv, w.dk, w.dv))
+    sub = {k: np.concatenate([v] * (n // ring), axis=1) for k, v in tok_np.items()}   # the ring, replayed
+    gdn.gdn_sequence(S0[:1], *(sub[x][:1, :2] for x in ("q", "k", "v", "g", "beta")))   # load the library
+    t0 = time.perf_counter()
+    _, _, _, used = gdn.gdn_sequence(S0, sub["q"], sub["k"], sub["v"], sub["g"], sub["beta"])
+    dt = time.perf_counter() - t0
+    return {"value": w.B * n / dt, "unit": "tokens/s/layer", "cores": used, "kind": "oracle",
+            "sample": "all %d requests x %d decode steps of the same workload (%.1f s)" % (w.B, n, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_19049_amd import kvb, synth, traffic
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    kvb.lib()   # fail loudly if the HIP library is missing
+    w = synth.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+
+    job = DecodeJob(w)
+    # untimed: build a real committed state by decoding a prompt-sized prefix, then W warm-up steps
+    job.run(w.prefix + W)
+    torch.cuda.synchronize()
+    t_start = job.t
+
+    graph = None
+    if args.mode == "graph":
+        snap = [x.clone() for x in (job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill)]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            job.run(K)
+        torch.cuda.synchronize()
+        # capture does not execute: put the counters back where the captured work expects them
+        for dst, src in zip((job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill), snap):
+            dst.copy_(src)
+        job.t = t_start
+        torch.cuda.synchronize()
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    e0.record()
+    if graph is not None:
+        graph.replay()
+        job.t = t_start + K
+    else:
+        job.run(K)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    sec = e0.elapsed_time(e1) * 1e-3
+    assert int(job.ds.status.sum().item()) == 0, "a buffer overflowed during the bench"
+
+    # same K steps again, eager, with HIP events around every decode launch: the dominant
+    # kernel's duration and its algorithmic bytes at the fill it actually ran at
+    events = []
+    job.run(K, events)
+    torch.cuda.synchronize()
+    dec_us = [a.elapsed_time(b) * 1e3 for a, b, _ in events]
+    units = w.B * w.Hv
+    dec_bytes = [traffic.total(traffic.decode_rw(traffic.KVB, f)) * units for _, _, f in events]
+    dec_avg_us = sum(dec_us) / len(dec_us)
+    achieved = sum(dec_bytes) / (sum(dec_us) * 1e-6) / 1e9
+    cycle_bytes = traffic.total(traffic.chunk_cycle_rw(traffic.KVB, w.C)) * units
+
+    res = {
+        "metric": "gdn_decode_tokens_per_s_per_layer", "value": w.B * K / sec, "unit": "tokens/s/layer",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": sec / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hk": w.Hk, "Hv": w.Hv, "dk": w.dk, "dv": w.dv,
+                   "C": w.C, "cap": w.cap, "in_dtype": w.in_dtype, "state_dtype": "f32",
+                   "step": "kvb_decode + kvb_flush(threshold=C)", "launch": args.mode,
+                   "state_MiB": units * w.dk * w.dv * 4 / 2 ** 20},
+        "full_cycle": {"algorithmic_bytes_per_step": cycle_bytes,
+                       "algorithmic_GBps": cycle_bytes / (sec / K) / 1e9,
+                       "frac_of_hbm_peak": cycle_bytes / (sec / K) / 1e9 / HBM_PEAK_GBS,
+                       "host_wall_ms_per_step": wall / K * 1e3},
+        "roofline": {"bound": "hbm", "kernel": "kvb_step_kernel<128,bf16,1> (kvb_decode)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_us": dec_avg_us, "launches": len(dec_us),
+                     "algorithmic_bytes_per_launch_avg": sum(dec_bytes) / len(dec_bytes),
+                     "timing": "HIP events around each kvb_decode launch, eager re-run of the same K steps"},
+    }
+    if not args.no_other_paths:
+        res["other_paths"] = time_other_paths(torch, kvb, synth, traffic)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, job.tok_np)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

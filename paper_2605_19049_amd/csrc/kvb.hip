@@ -47,6 +47,39 @@ __device__ __forceinline__ void load8(const bf16_t *p, float (&o)[8])
     o[6] = __uint_as_float(w.w << 16); o[7] = __uint_as_float(w.w & 0xFFFF0000u);
 }
 
+// The same 8 elements as untouched bits: issuing a load and converting its result are
+// kept apart so that no wait lands between two loads.
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<float> {
+    float4 a, b;
+};
+template <>
+struct Raw8<bf16_t> {
+    uint4 w;
+};
+__device__ __forceinline__ Raw8<float> load_raw8(const float *p)
+{
+    return Raw8<float>{*reinterpret_cast<const float4 *>(p), *reinterpret_cast<const float4 *>(p + 4)};
+}
+__device__ __forceinline__ Raw8<bf16_t> load_raw8(const bf16_t *p)
+{
+    return Raw8<bf16_t>{*reinterpret_cast<const uint4 *>(p)};
+}
+__device__ __forceinline__ void unpack8(const Raw8<float> &r, float (&o)[8])
+{
+    o[0] = r.a.x; o[1] = r.a.y; o[2] = r.a.z; o[3] = r.a.w;
+    o[4] = r.b.x; o[5] = r.b.y; o[6] = r.b.z; o[7] = r.b.w;
+}
+__device__ __forceinline__ void unpack8(const Raw8<bf16_t> &r, float (&o)[8])
+{
+    o[0] = __uint_as_float(r.w.x << 16); o[1] = __uint_as_float(r.w.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(r.w.y << 16); o[3] = __uint_as_float(r.w.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(r.w.z << 16); o[5] = __uint_as_float(r.w.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(r.w.w << 16); o[7] = __uint_as_float(r.w.w & 0xFFFF0000u);
+}
+
 __device__ __forceinline__ void fma4(float4 &acc, float c, const float4 &x)
 {
     acc.x = fmaf(c, x.x, acc.x);
@@ -58,12 +91,47 @@ __device__ __forceinline__ void fma4(float4 &acc, float c, const float4 &x)
 // The workgroups of one request share fill[slot].  Each reads it (low 16 bits)
 // when it starts and takes a ticket (bits 16..) when it has finished; the
 // workgroup holding the last ticket knows every other one has read the word and
-// stores the new plain value.
+// stores the new plain value.  Relaxed ordering is enough and matters: a
+// workgroup's read of the word has long completed when it takes its ticket
+// (its value fed address computations), the store depends on the ticket's
+// return value, and nothing else is communicated through the word.  Acquire /
+// release ordering at device scope would make every workgroup write back and
+// invalidate its L2, which costs more than the kernel's whole memory traffic.
+//
+// The ticket is taken right after the read (take_ticket), so that its round trip
+// overlaps the workgroup's streaming, and is looked at only at the very end.
+__device__ __forceinline__ int take_ticket(int32_t *word)
+{
+    return __hip_atomic_fetch_add(word, TICKET_ONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_if_last(int32_t *word, int ticket, int nwg, int new_fill)
+{
+    if ((ticket >> 16) == nwg - 1)
+        __hip_atomic_store(word, new_fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void publish_fill(int32_t *word, int nwg, int new_fill)
 {
-    const int old = __hip_atomic_fetch_add(word, TICKET_ONE, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    if ((old >> 16) == nwg - 1)
-        __hip_atomic_store(word, new_fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    publish_if_last(word, take_ticket(word), nwg, new_fill);
+}
+
+__device__ __forceinline__ void store_raw8(float *p, const Raw8<float> &r)
+{
+    *reinterpret_cast<float4 *>(p) = r.a;
+    *reinterpret_cast<float4 *>(p + 4) = r.b;
+}
+__device__ __forceinline__ void store_raw8(bf16_t *p, const Raw8<bf16_t> &r)
+{
+    *reinterpret_cast<uint4 *>(p) = r.w;
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Map them so
+// that XCD x works on one contiguous eighth of the (request, head) units: all heads of a
+// request then share an L2, which keeps the per-request ticket atomics and the keys that
+// grouped heads share inside one XCD.
+__device__ __forceinline__ int logical_block()
+{
+    const int n = gridDim.x, x = blockIdx.x;
+    return (n % 8 == 0) ? (x % 8) * (n / 8) + x / 8 : x;
 }
 
 struct Store {
@@ -93,33 +161,53 @@ struct StepArgs {
 //   accU_i = -gamma_i k_i S0 - sum_{l<f} Gamma_il (k_i.k_l) u_l
 //   accO_i =  gamma_i q_i S0 + sum_{l<f} Gamma_il (q_i.k_l) u_l
 // are accumulated over state rows and buffered records alike (both are "rows"
-// weighted by a per-row scalar), reduced across the workgroup, and the T drafts
-// are then finished by forward substitution among themselves.
+// weighted by a per-row scalar), reduced across the workgroup, and the T new
+// rows are then finished by forward substitution among themselves.
+//
+// Load order is the point of this kernel.  The memory counter retires loads
+// in issue order, so the few small loads whose values are needed first (new
+// q/k rows, the buffered records of a WREC-record window, v) are issued
+// before the 64 KB state tile; the dot products and the LDS exchange then run
+// while the state is still in flight.
 // ---------------------------------------------------------------------------
-template <int D, typename TIn, int TM>
+template <int N>
+__device__ __forceinline__ float group_sum(float x)
+{
+#pragma unroll
+    for (int off = 1; off < N; off <<= 1)
+        x += __shfl_xor(x, off);
+    return x;
+}
+
+template <int D, typename TIn, int TM, int WREC, bool HAS_STATE>
 __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
 {
     constexpr int LPR = D / 4;       // lanes covering one state row with float4
     constexpr int RPP = NT / LPR;    // rows covered by the workgroup per pass
-    constexpr int NPASS = D / RPP;   // rows per thread
+    constexpr int NPASS = D / RPP;   // state rows per thread
     constexpr int GL = D / 8;        // lanes sharing one key dot product (8 elements each)
     constexpr int NG = NT / GL;      // records handled per pass of the dot-product phase
+    constexpr int KP = (WREC + NG - 1) / NG;    // key passes held in registers
+    constexpr int UP = (WREC + RPP - 1) / RPP;  // delta-value passes held in registers
     constexpr int NC = KVB_MAX_CAP + TM;
+    // the two smaller window tiers are only launched when the whole buffer fits the window
+    constexpr bool TAIL = WREC >= 64;
 
-    __shared__ float sKs[TM][D];     // -gamma_i * k_i   (weights of the state rows for accU)
-    __shared__ float sQs[TM][D];     //  gamma_i * q_i
-    __shared__ float rK[TM][D];      // raw k_i, q_i
-    __shared__ float rQ[TM][D];
+    __shared__ __attribute__((aligned(16))) float sKs[TM][D];  // -gamma_i k_i (state-row weights for accU)
+    __shared__ __attribute__((aligned(16))) float sQs[TM][D];  //  gamma_i q_i
+    __shared__ __attribute__((aligned(16))) float rK[TM][D];   // raw new rows
+    __shared__ __attribute__((aligned(16))) float rQ[TM][D];
     __shared__ float cK[TM][NC];     // Gamma_il (k_i.k_l), 0 for l >= f+i
     __shared__ float cQ[TM][NC];     // Gamma_il (q_i.k_l), 0 for l >  f+i
-    __shared__ float red[NW][TM][2][D];
+    __shared__ __attribute__((aligned(16))) float red[NW][TM][2][D];
 
     const int tid = threadIdx.x;
-    const int b = blockIdx.x / a.Hv;
-    const int h = blockIdx.x % a.Hv;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
     const int r = a.Hv / a.Hk;
     const int hk = h / r;
-    const int T = a.T;
+    const int T = TM == 1 ? 1 : a.T;
     const int cap = a.cap;
 
     const int s = a.slot[b];
@@ -136,22 +224,18 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         return;
     }
 
-    const int rg = tid / LPR;
-    const int c4 = tid % LPR;
+    const int rg = tid / LPR, c4 = tid % LPR;
+    const int grp = tid / GL, sub = tid % GL;
     const size_t unit = (size_t)s * a.Hv + h;
-
-    // 1. put the whole state tile in flight
-    float4 sreg[NPASS];
-    const bool has_state = a.st.state != nullptr;
-    if (has_state) {
-        const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p)
-            sreg[p] = sp[(size_t)(rg + RPP * p) * LPR + c4];
-    }
-
-    // 2. per-draft scalars and the new q, k rows
+    const TIn *qin = static_cast<const TIn *>(a.q);
+    const TIn *kin = static_cast<const TIn *>(a.k);
+    const TIn *vin = static_cast<const TIn *>(a.v);
     const float *Gbuf = a.st.buf_G + unit * cap;
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
+    const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u + unit * cap * D);
+
+    // ---- 1. small loads --------------------------------------------------
+    // per-draft scalars (uniform)
     float Gc[TM], bet[TM];
     {
         float run = f > 0 ? Gbuf[f - 1] : 0.0f;
@@ -166,101 +250,222 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             Gc[i] = run;
         }
     }
-    const TIn *qin = static_cast<const TIn *>(a.q);
-    const TIn *kin = static_cast<const TIn *>(a.k);
-    if (tid < D) {
+    // All loads below are issued as raw bits from always-valid addresses (an index past
+    // the fill is clamped to record 0 and its value ignored), with no branch and no
+    // conversion in between, so nothing waits before the state tile is in flight.
+    // new rows: each thread's 8-element slice of q_i, k_i (TM > 1: thread idx -> row idx / (D/8))
+    const int nr_i = TM == 1 ? 0 : min(tid / (D / 8), T - 1);
+    const int nr_e = TM == 1 ? sub : tid % (D / 8);
+    const size_t nr_o = (((size_t)b * T + nr_i) * a.Hk + hk) * D + 8 * nr_e;
+    const Raw8<TIn> q_raw = load_raw8(qin + nr_o);
+    const Raw8<TIn> k_raw = load_raw8(kin + nr_o);
+    // window of buffered records
+    Raw8<TIn> kl_raw[KP];
+    float Gl[KP];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i < T) {
-                const size_t o = (((size_t)b * T + i) * a.Hk + hk) * D + tid;
-                const float kv = to_f32(kin[o]);
-                const float qv = to_f32(qin[o]);
-                const float gam = expf(Gc[i]);
-                rK[i][tid] = kv;
-                rQ[i][tid] = qv;
-                sKs[i][tid] = -gam * kv;
-                sQs[i][tid] = gam * qv;
+    for (int p = 0; p < KP; ++p) {
+        const int l = grp + NG * p;
+        const int lc = l < f ? l : 0;
+        kl_raw[p] = load_raw8(kb + (size_t)lc * D + 8 * sub);
+        Gl[p] = Gbuf[lc];
+    }
+    float4 ur[UP];
+#pragma unroll
+    for (int j = 0; j < UP; ++j) {
+        const int l = rg + RPP * j;
+        ur[j] = up[(size_t)(l < f ? l : 0) * LPR + c4];
+    }
+    TIn v_raw[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + tid % D];
+
+    // ---- 2. the state tile goes in flight ---------------------------------
+    float4 sreg[NPASS];
+    if constexpr (HAS_STATE) {
+        const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p)
+            sreg[p] = sp[(size_t)(rg + RPP * p) * LPR + c4];
+    }
+    // youngest memory operation of the wave: nothing waits for it before the very end
+    int ticket = 0;
+    if (a.advance && tid == 0)
+        ticket = take_ticket(&a.st.fill[s]);
+
+    // ---- 3. decayed dot products of the new rows with every earlier key ----
+    float q8[8], k8[8];
+    unpack8(q_raw, q8);
+    unpack8(k_raw, k8);
+    if constexpr (TM == 1) {
+        const float gam = expf(Gc[0]);
+        if (grp == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                sKs[0][8 * sub + e] = -gam * k8[e];
+                sQs[0][8 * sub + e] = gam * q8[e];
             }
         }
-    }
-    __syncthreads();
-
-    // 3. decayed dot products of the new rows with every earlier key
-    {
-        const int grp = tid / GL, sub = tid % GL;
-        const int nrec = f + T;
-        const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
-        for (int base = 0; base < nrec; base += NG) {
-            const int l = base + grp;
-            if (l < nrec) {
-                float kl[8];
-                float Gl;
-                if (l < f) {
-                    load8(kb + (size_t)l * D + 8 * sub, kl);
-                    Gl = Gbuf[l];
-                } else {
+        float dqk = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        kl[e] = rK[l - f][8 * sub + e];
-                    Gl = 0.0f;  // set per draft below
-                }
+        for (int e = 0; e < 8; ++e)
+            dqk = fmaf(q8[e], k8[e], dqk);
+        dqk = group_sum<GL>(dqk);
+        if (tid == 0) {
+            cK[0][f] = 0.0f;
+            cQ[0][f] = dqk;
+        }
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    if (i < T) {
-                        float dkk = 0.0f, dqk = 0.0f;
+        for (int p = 0; p < KP; ++p) {
+            const int l = grp + NG * p;
+            float kx[8];
+            unpack8(kl_raw[p], kx);
+            float dkk = 0.0f, dq = 0.0f;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            dkk = fmaf(kl[e], rK[i][8 * sub + e], dkk);
-                            dqk = fmaf(kl[e], rQ[i][8 * sub + e], dqk);
-                        }
+            for (int e = 0; e < 8; ++e) {
+                dkk = fmaf(kx[e], k8[e], dkk);
+                dq = fmaf(kx[e], q8[e], dq);
+            }
+            dkk = group_sum<GL>(dkk);
+            dq = group_sum<GL>(dq);
+            if (sub == 0 && l < f) {
+                const float w = expf(Gc[0] - Gl[p]);
+                cK[0][l] = w * dkk;
+                cQ[0][l] = w * dq;
+            }
+        }
+        for (int l = KP * NG + grp; TAIL && l < f; l += NG) {   // records beyond the register window
+            float kx[8];
+            load8(kb + (size_t)l * D + 8 * sub, kx);
+            float dkk = 0.0f, dq = 0.0f;
 #pragma unroll
-                        for (int off = 1; off < GL; off <<= 1) {
-                            dkk += __shfl_xor(dkk, off);
-                            dqk += __shfl_xor(dqk, off);
-                        }
-                        if (sub == 0) {
-                            const int li = f + i;
-                            float gl = Gl;
-                            if (l >= f) {
-                                // G of draft l-f: Gc[] indexed statically
-                                gl = 0.0f;
+            for (int e = 0; e < 8; ++e) {
+                dkk = fmaf(kx[e], k8[e], dkk);
+                dq = fmaf(kx[e], q8[e], dq);
+            }
+            dkk = group_sum<GL>(dkk);
+            dq = group_sum<GL>(dq);
+            if (sub == 0) {
+                const float w = expf(Gc[0] - Gbuf[l]);
+                cK[0][l] = w * dkk;
+                cQ[0][l] = w * dq;
+            }
+        }
+    } else {
+        if (tid < T * (D / 8)) {
+            float gam = 0.0f;
 #pragma unroll
-                                for (int j = 0; j < TM; ++j)
-                                    if (j == l - f)
-                                        gl = Gc[j];
-                            }
-                            const float gam = l <= li ? expf(Gc[i] - gl) : 0.0f;
-                            cK[i][l] = l < li ? gam * dkk : 0.0f;
-                            cQ[i][l] = gam * dqk;
-                        }
+            for (int j = 0; j < TM; ++j)
+                if (j == nr_i)
+                    gam = expf(Gc[j]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                rK[nr_i][8 * nr_e + e] = k8[e];
+                rQ[nr_i][8 * nr_e + e] = q8[e];
+                sKs[nr_i][8 * nr_e + e] = -gam * k8[e];
+                sQs[nr_i][8 * nr_e + e] = gam * q8[e];
+            }
+        }
+        __syncthreads();   // rK, rQ visible
+        // buffered records, all T new rows at once
+        auto rows_vs_record = [&](const float(&kx)[8], float Gx, int l) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if (i < T) {
+                    float dkk = 0.0f, dq = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        dkk = fmaf(kx[e], rK[i][8 * sub + e], dkk);
+                        dq = fmaf(kx[e], rQ[i][8 * sub + e], dq);
+                    }
+                    dkk = group_sum<GL>(dkk);
+                    dq = group_sum<GL>(dq);
+                    if (sub == 0 && l < f) {
+                        const float w = expf(Gc[i] - Gx);
+                        cK[i][l] = w * dkk;
+                        cQ[i][l] = w * dq;
                     }
                 }
             }
+        };
+#pragma unroll
+        for (int p = 0; p < KP; ++p) {
+            float kx[8];
+            unpack8(kl_raw[p], kx);
+            rows_vs_record(kx, Gl[p], grp + NG * p);
+        }
+        for (int l0 = KP * NG; TAIL && l0 < f; l0 += NG) {
+            const int l = l0 + grp;
+            float kx[8];
+            float Gx = 0.0f;
+            if (l < f) {
+                load8(kb + (size_t)l * D + 8 * sub, kx);
+                Gx = Gbuf[l];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    kx[e] = 0.0f;
+            }
+            rows_vs_record(kx, Gx, l);
+        }
+        // new rows against each other: pair (i, j <= i) -> columns f+j of row i
+        for (int pr = grp; pr < T * T; pr += NG) {
+            const int i = pr / T, j = pr % T;
+            float dkk = 0.0f, dq = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float kj = rK[j][8 * sub + e];
+                dkk = fmaf(kj, rK[i][8 * sub + e], dkk);
+                dq = fmaf(kj, rQ[i][8 * sub + e], dq);
+            }
+            dkk = group_sum<GL>(dkk);
+            dq = group_sum<GL>(dq);
+            if (sub == 0) {
+                float Gi = 0.0f, Gj = 0.0f;
+#pragma unroll
+                for (int x = 0; x < TM; ++x) {
+                    if (x == i) Gi = Gc[x];
+                    if (x == j) Gj = Gc[x];
+                }
+                const float w = j <= i ? expf(Gi - Gj) : 0.0f;
+                cK[i][f + j] = j < i ? w * dkk : 0.0f;
+                cQ[i][f + j] = w * dq;
+            }
         }
     }
     __syncthreads();
 
-    // 4. accumulate over buffered records and state rows
+    // ---- 4. accumulate over buffered records and state rows ----------------
     float4 accU[TM], accO[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         accU[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         accO[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    {
-        const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u + unit * cap * D);
-        for (int l = rg; l < f; l += RPP) {
-            const float4 u = up[(size_t)l * LPR + c4];
+#pragma unroll
+    for (int j = 0; j < UP; ++j) {
+        const int l = rg + RPP * j;
+        if (l < f) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 if (i < T) {
-                    fma4(accU[i], -cK[i][l], u);
-                    fma4(accO[i], cQ[i][l], u);
+                    fma4(accU[i], -cK[i][l], ur[j]);
+                    fma4(accO[i], cQ[i][l], ur[j]);
                 }
             }
         }
     }
-    if (has_state) {
+    for (int l = UP * RPP + rg; TAIL && l < f; l += RPP) {
+        const float4 u = up[(size_t)l * LPR + c4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i < T) {
+                fma4(accU[i], -cK[i][l], u);
+                fma4(accO[i], cQ[i][l], u);
+            }
+        }
+    }
+    if constexpr (HAS_STATE) {
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             const int row = rg + RPP * p;
@@ -274,7 +479,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         }
     }
 
-    // 5. reduce over the row groups: inside the wave by shuffles, across waves via LDS
+    // ---- 5. reduce over the row groups: shuffles inside the wave, LDS across waves
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         if (i < T) {
@@ -305,9 +510,8 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     }
     __syncthreads();
 
-    // 6. finish the T new rows (forward substitution among the drafts), write results
+    // ---- 6. finish the T new rows (forward substitution), write results -----
     if (tid < D) {
-        const TIn *vin = static_cast<const TIn *>(a.v);
         float uprev[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -319,7 +523,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                     ao += red[w][i][1][tid];
                 }
                 const size_t row = ((size_t)b * T + i) * a.Hv + h;
-                float acc = to_f32(vin[row * D + tid]) + au;
+                float acc = to_f32(v_raw[i]) + au;
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
                     if (j < i)
@@ -344,19 +548,18 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                 gv = Gc[j];
         a.st.buf_G[unit * cap + f + tid] = gv;
     }
-    if (h % r == 0) {
-        TIn *kb = static_cast<TIn *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f) * D;
-        for (int idx = tid; idx < T * D; idx += NT) {
-            const int i = idx / D, e = idx % D;
-            kb[(size_t)i * D + e] = kin[(((size_t)b * T + i) * a.Hk + hk) * D + e];
-        }
+    if (h % r == 0 && tid < T * (D / 8)) {   // the threads that loaded the new k rows store them
+        TIn *kw = static_cast<TIn *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f) * D;
+        store_raw8(kw + (size_t)nr_i * D + 8 * nr_e, k_raw);
     }
     if (a.advance && tid == 0)
-        publish_fill(&a.st.fill[s], a.Hv, f + T);
+        publish_if_last(&a.st.fill[s], ticket, a.Hv, f + T);
 }
 
 // ---------------------------------------------------------------------------
 // kvb_flush: S <- gamma_{m-1} S + sum_{l<m} Gamma_{m-1,l} k_l^T u_l   (Eq. 16, last line)
+// The rank-m sum is accumulated apart from the state so that the state tile can
+// stay in flight until the very end.
 // ---------------------------------------------------------------------------
 struct FlushArgs {
     Store st;
@@ -371,14 +574,16 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
     constexpr int LPR = D / 4;
     constexpr int RPP = NT / LPR;
     constexpr int NPASS = D / RPP;
-    constexpr int LT = 16;  // records staged per LDS tile
+    constexpr int LT = 16;                  // records staged per LDS tile
+    constexpr int EPT = LT * D / NT;        // tile elements per thread
 
-    __shared__ float kh[LT][D];  // Gamma_{m-1,l} k_l
-    __shared__ float uu[LT][D];
+    __shared__ __attribute__((aligned(16))) float kh[LT][D];  // Gamma_{m-1,l} k_l
+    __shared__ __attribute__((aligned(16))) float uu[LT][D];
 
     const int tid = threadIdx.x;
-    const int b = blockIdx.x / a.Hv;
-    const int h = blockIdx.x % a.Hv;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
     const int hk = h / (a.Hv / a.Hk);
     const int cap = a.cap;
 
@@ -396,46 +601,76 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
             atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
     }
     const bool do_flush = m >= a.threshold && m > 0;
-    if (do_flush) {
-        const int rg = tid / LPR, c4 = tid % LPR;
-        const size_t unit = (size_t)s * a.Hv + h;
-        float4 *sp = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
-        float4 sreg[NPASS];
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p)
-            sreg[p] = sp[(size_t)(rg + RPP * p) * LPR + c4];
+    if (!do_flush) {
+        if (m != f && tid == 0)   // fill only moves when something was accepted
+            publish_fill(&a.st.fill[s], a.Hv, m);
+        return;
+    }
+    int ticket = 0;
+    if (tid == 0)
+        ticket = take_ticket(&a.st.fill[s]);
+    const int rg = tid / LPR, c4 = tid % LPR;
+    const size_t unit = (size_t)s * a.Hv + h;
+    const float *Gbuf = a.st.buf_G + unit * cap;
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
+    const float *ub = a.st.buf_u + unit * cap * D;
+    const float Glast = Gbuf[m - 1];
 
-        const float *Gbuf = a.st.buf_G + unit * cap;
-        const float Glast = Gbuf[m - 1];
-        const float gam = expf(Glast);
+    // first record tile, then the state tile, so the tile's loads retire first
+    float kt[EPT], ut[EPT];
+    auto load_tile = [&](int l0) {
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            sreg[p].x *= gam; sreg[p].y *= gam; sreg[p].z *= gam; sreg[p].w *= gam;
-        }
-        const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
-        const float *ub = a.st.buf_u + unit * cap * D;
-        for (int l0 = 0; l0 < m; l0 += LT) {
-            const int nl = min(LT, m - l0);
-            for (int idx = tid; idx < nl * D; idx += NT) {
-                const int l = idx / D, e = idx % D;
-                kh[l][e] = expf(Glast - Gbuf[l0 + l]) * to_f32(kb[(size_t)(l0 + l) * D + e]);
-                uu[l][e] = ub[(size_t)(l0 + l) * D + e];
+        for (int x = 0; x < EPT; ++x) {
+            const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
+            if (l < m) {
+                kt[x] = expf(Glast - Gbuf[l]) * to_f32(kb[(size_t)l * D + e]);
+                ut[x] = ub[(size_t)l * D + e];
+            } else {
+                kt[x] = 0.0f;
+                ut[x] = 0.0f;
             }
-            __syncthreads();
-            for (int l = 0; l < nl; ++l) {
-                const float4 u = *reinterpret_cast<const float4 *>(&uu[l][4 * c4]);
+        }
+    };
+    load_tile(0);
+    float4 *sp = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
+    float4 sreg[NPASS], dS[NPASS];
 #pragma unroll
-                for (int p = 0; p < NPASS; ++p)
-                    fma4(sreg[p], kh[l][rg + RPP * p], u);
-            }
+    for (int p = 0; p < NPASS; ++p) {
+        sreg[p] = sp[(size_t)(rg + RPP * p) * LPR + c4];
+        dS[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int l0 = 0; l0 < m; l0 += LT) {
+        if (l0 > 0) {
             __syncthreads();
+            load_tile(l0);
         }
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p)
-            sp[(size_t)(rg + RPP * p) * LPR + c4] = sreg[p];
+        for (int x = 0; x < EPT; ++x) {
+            const int idx = tid + NT * x;
+            kh[idx / D][idx % D] = kt[x];
+            uu[idx / D][idx % D] = ut[x];
+        }
+        __syncthreads();
+        const int nl = min(LT, m - l0);
+        for (int l = 0; l < nl; ++l) {
+            const float4 u = *reinterpret_cast<const float4 *>(&uu[l][4 * c4]);
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p)
+                fma4(dS[p], kh[l][rg + RPP * p], u);
+        }
+    }
+    const float gam = expf(Glast);
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+        float4 o;
+        o.x = fmaf(gam, sreg[p].x, dS[p].x);
+        o.y = fmaf(gam, sreg[p].y, dS[p].y);
+        o.z = fmaf(gam, sreg[p].z, dS[p].z);
+        o.w = fmaf(gam, sreg[p].w, dS[p].w);
+        sp[(size_t)(rg + RPP * p) * LPR + c4] = o;
     }
     if (tid == 0)
-        publish_fill(&a.st.fill[s], a.Hv, do_flush ? 0 : m);
+        publish_if_last(&a.st.fill[s], ticket, a.Hv, 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -468,8 +703,9 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
     __shared__ float sB[LM];
 
     const int tid = threadIdx.x;
-    const int b = blockIdx.x / a.Hv;
-    const int h = blockIdx.x % a.Hv;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
     const int r = a.Hv / a.Hk;
     const int hk = h / r;
     const int Lmax = a.Lmax;
@@ -608,17 +844,37 @@ int finish_launch()
     return KVB_OK;
 }
 
+template <int D, typename TIn, int TM, int WREC>
+void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
+{
+    if (a.st.state)
+        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, TM, WREC, true>), dim3(blocks), dim3(NT), 0, stream, a);
+    else
+        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, TM, WREC, false>), dim3(blocks), dim3(NT), 0, stream, a);
+}
+
+template <int D, typename TIn, int TM>
+void launch_step_w(const StepArgs &a, int blocks, hipStream_t stream)
+{
+    // Register window of buffered records.  For d = 128 the smallest tier that holds the
+    // whole buffer is used; the smaller head sizes only carry the general (64 + tail) tier.
+    if (D == 128 && a.cap <= 16)
+        launch_step_s<D, TIn, TM, D == 128 ? 16 : 64>(a, blocks, stream);
+    else if (D == 128 && a.cap <= 32)
+        launch_step_s<D, TIn, TM, D == 128 ? 32 : 64>(a, blocks, stream);
+    else
+        launch_step_s<D, TIn, TM, 64>(a, blocks, stream);
+}
+
 template <int D, typename TIn>
 void launch_step(const StepArgs &a, int blocks, hipStream_t stream)
 {
     if (a.T == 1)
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, 1>), dim3(blocks), dim3(NT), 0, stream, a);
-    else if (a.T == 2)
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, 2>), dim3(blocks), dim3(NT), 0, stream, a);
+        launch_step_w<D, TIn, 1>(a, blocks, stream);
     else if (a.T <= 4)
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, 4>), dim3(blocks), dim3(NT), 0, stream, a);
+        launch_step_w<D, TIn, 4>(a, blocks, stream);
     else
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, 8>), dim3(blocks), dim3(NT), 0, stream, a);
+        launch_step_w<D, TIn, 8>(a, blocks, stream);
 }
 
 // Calls f.template operator()<D, TIn>() for the compiled (head size, dtype) pairs.

@@ -128,6 +128,29 @@ def kvb_direct(sh, st, slot, lens, Lmax, q, k, v, g, beta, out, stream=None, che
     return _check(rc, "kvb_direct", check)
 
 
+def bind(fn_name, *args):
+    """Pre-marshal one call: returns a zero-argument callable that re-issues it with the
+    same pointers (for serving loops, where per-call marshalling would rival a 20 us
+    kernel).  `args` are exactly the C arguments; tensors, structs and ints are converted
+    once.  The caller keeps the tensors and structs alive."""
+    fn = getattr(lib(), fn_name)
+    conv = []
+    for a, t in zip(args, fn.argtypes):
+        if isinstance(a, ctypes.Structure):
+            conv.append(ctypes.byref(a))
+        elif t is ctypes.c_void_p:
+            conv.append(ctypes.c_void_p(_ptr(a)))
+        else:
+            conv.append(t(a))
+    assert len(conv) == len(fn.argtypes), fn_name
+
+    def call():
+        rc = fn(*conv)
+        if rc != OK:
+            raise KvbError(rc, fn_name)
+    return call
+
+
 class DeviceStore:
     """Caller-side holder of the device arrays of include/kvb.h's kvb_store, allocated
     with PyTorch (memory plumbing only)."""

@@ -385,3 +385,45 @@ def test_snapshot_restore_mid_chunk():
     steps(5, 12, out2)
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
+
+
+def test_hip_graph_replays_match_eager():
+    """The decode + flush loop captured in a HIP graph: every replay, with eager work and
+    synchronisation in between, gives the eager loop's outputs and state bit for bit."""
+    rng = np.random.default_rng(76)
+    B, Hk, Hv, d, C, n = 4, 2, 4, 128, 4, 10
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    dt = H.upload_tokens(synth.token_stream(rng, B, n, Hk, Hv, d, d, "bf16"), "bf16")
+    toks = [H.step_view(dt, t) for t in range(n)]
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+    outs = torch.zeros((n, B, Hv, d), dtype=torch.float32, device="cuda")
+    bufs = (lay.ds.state, lay.ds.buf_k, lay.ds.buf_u, lay.ds.buf_G, lay.ds.fill)
+
+    def loop():
+        for t in range(n):
+            lay.decode(toks[t], outs[t])
+            lay.flush(C)
+
+    def reset():
+        lay.ds.buf_k.zero_(); lay.ds.buf_u.zero_(); lay.ds.buf_G.zero_(); lay.ds.fill.zero_()
+        lay.set_state(S0)
+        outs.zero_()
+
+    reset()
+    loop()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in bufs + (outs,)]
+    reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        loop()
+    for rep in range(4):
+        reset()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(bufs + (outs,), want):
+            assert torch.equal(got, ref), "replay %d differs from eager" % rep
+        loop()                       # eager work between replays
+        torch.cuda.synchronize()
