@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the KVBuffer GDN decode path on one MI355X.
 
-One "step" = one chunkwise decoding step of the whole batch through one GDN layer:
-kvb_decode followed by kvb_flush(threshold = C) (the flush call is issued every step; its
-device-side predicate makes it a no-op until the buffer holds C records).  The headline
-workload is the Qwen3-Next-shaped layer: batch 64, 16 qk + 32 v heads, d = 128, bf16
-q/k/v, fp32 state, C = 16.  Prints ONE JSON line.
+One "step" = one chunkwise decoding step of the whole batch through one GDN layer, state
+update included: either the single-kernel kvb_decode_flush(threshold = C) (--step fused,
+default) or kvb_decode followed by kvb_flush(threshold = C) (--step split: the paper's
+two-kernel arrangement; the flush call is issued every step and its device-side predicate
+makes it a no-op until the buffer holds C records).  The headline workload is the
+Qwen3-Next-shaped layer: batch 64, 16 qk + 32 v heads, d = 128, bf16 q/k/v, fp32 state,
+C = 16.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -25,6 +27,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="qwen3next_decode")
+    ap.add_argument("--step", choices=["fused", "split"], default="fused")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the K timed steps are one HIP graph launch; eager: one launch per kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -35,7 +38,7 @@ def parse():
 class DecodeJob:
     """Device-resident workload: store, a ring of token inputs, pre-marshalled calls."""
 
-    def __init__(self, w, ring=64):
+    def __init__(self, w, ring=64, fused=True):
         import numpy as np
         import torch
         from paper_2605_19049_amd import kvb, synth
@@ -60,33 +63,40 @@ class DecodeJob:
                 "beta": torch.from_numpy(tok["beta"][:, t].copy()).cuda()})
         self.out = torch.empty((w.B, w.Hv, w.dv), dtype=torch.float32, device="cuda")
         self.t = 0          # tokens decoded so far (selects the ring entry)
+        self.fused = fused
         self._bound = {}
 
     def _calls(self, stream):
         key = stream
         if key not in self._bound:
             kvb = self.kvb
-            dec = [kvb.bind("kvb_decode", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
-                            x["beta"], self.out, stream) for x in self.tok]
-            fl = kvb.bind("kvb_flush", self.sh, self.st, self.slot, None, self.w.C, stream)
+            if self.fused:
+                dec = [kvb.bind("kvb_decode_flush", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
+                                x["beta"], self.out, self.w.C, stream) for x in self.tok]
+                fl = None
+            else:
+                dec = [kvb.bind("kvb_decode", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
+                                x["beta"], self.out, stream) for x in self.tok]
+                fl = kvb.bind("kvb_flush", self.sh, self.st, self.slot, None, self.w.C, stream)
             self._bound[key] = (dec, fl)
         return self._bound[key]
 
-    def run(self, n, events=None):
-        """n steps on the current stream; with `events`, bracket every decode launch."""
+    def run(self, n, timers=None):
+        """n steps on the current stream; with `timers` (a list to fill), every decode launch
+        carries a kvb timer, which records that kernel's own begin/end timestamps."""
         torch = self.torch
         dec, fl = self._calls(torch.cuda.current_stream().cuda_stream)
         for _ in range(n):
             d = dec[self.t % self.ring]
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
+            if timers is not None:
+                tm = self.kvb.Timer()
+                tm.arm()
                 d()
-                e1.record()
-                events.append((e0, e1, self.t % self.w.C))
+                timers.append((tm, self.t % self.w.C))
             else:
                 d()
-            fl()
+            if fl is not None:
+                fl()
             self.t += 1
 
 
@@ -187,21 +197,23 @@ def main():
     w = synth.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
 
-    job = DecodeJob(w)
+    fused = args.step == "fused"
+    job = DecodeJob(w, fused=fused)
     # untimed: build a real committed state by decoding a prompt-sized prefix, then W warm-up steps
     job.run(w.prefix + W)
     torch.cuda.synchronize()
     t_start = job.t
+    bufs = (job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill)
 
     graph = None
     if args.mode == "graph":
-        snap = [x.clone() for x in (job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill)]
+        snap = [x.clone() for x in bufs]
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             job.run(K)
         torch.cuda.synchronize()
-        # capture does not execute: put the counters back where the captured work expects them
-        for dst, src in zip((job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill), snap):
+        # make sure the store is exactly where the captured work expects it
+        for dst, src in zip(bufs, snap):
             dst.copy_(src)
         job.t = t_start
         torch.cuda.synchronize()
@@ -221,17 +233,29 @@ def main():
     sec = e0.elapsed_time(e1) * 1e-3
     assert int(job.ds.status.sum().item()) == 0, "a buffer overflowed during the bench"
 
-    # same K steps again, eager, with HIP events around every decode launch: the dominant
-    # kernel's duration and its algorithmic bytes at the fill it actually ran at
-    events = []
-    job.run(K, events)
+    # The same K steps again, eager, every decode launch carrying a kernel timer (begin/end
+    # timestamps of that kernel alone): the dominant kernel's duration, with its algorithmic
+    # bytes at the fill it actually ran at.
+    timers = []
+    job.run(K, timers)
     torch.cuda.synchronize()
-    dec_us = [a.elapsed_time(b) * 1e3 for a, b, _ in events]
     units = w.B * w.Hv
-    dec_bytes = [traffic.total(traffic.decode_rw(traffic.KVB, f)) * units for _, _, f in events]
+    dec_us = [tm.us() for tm, _ in timers]
+    if fused:
+        dec_bytes = [traffic.total(traffic.decode_flush_rw(traffic.KVB, f, w.C)) * units for _, f in timers]
+        cycle_bytes = traffic.total(traffic.fused_cycle_rw(traffic.KVB, w.C)) * units
+        kname = "kvb_step_kernel<128,bf16,TM=1,W=16,state,fused> (kvb_decode_flush)"
+        step_desc = "kvb_decode_flush(threshold=C)"
+    else:
+        dec_bytes = [traffic.total(traffic.decode_rw(traffic.KVB, f)) * units for _, f in timers]
+        cycle_bytes = traffic.total(traffic.chunk_cycle_rw(traffic.KVB, w.C)) * units
+        kname = "kvb_step_kernel<128,bf16,TM=1,W=16,state> (kvb_decode)"
+        step_desc = "kvb_decode + kvb_flush(threshold=C)"
+    for tm, _ in timers:
+        tm.close()
     dec_avg_us = sum(dec_us) / len(dec_us)
     achieved = sum(dec_bytes) / (sum(dec_us) * 1e-6) / 1e9
-    cycle_bytes = traffic.total(traffic.chunk_cycle_rw(traffic.KVB, w.C)) * units
+    noflush = [(u, b) for u, b, (_, f) in zip(dec_us, dec_bytes, timers) if f + 1 < w.C]
 
     res = {
         "metric": "gdn_decode_tokens_per_s_per_layer", "value": w.B * K / sec, "unit": "tokens/s/layer",
@@ -240,18 +264,22 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hk": w.Hk, "Hv": w.Hv, "dk": w.dk, "dv": w.dv,
                    "C": w.C, "cap": w.cap, "in_dtype": w.in_dtype, "state_dtype": "f32",
-                   "step": "kvb_decode + kvb_flush(threshold=C)", "launch": args.mode,
+                   "step": step_desc, "launch": args.mode,
                    "state_MiB": units * w.dk * w.dv * 4 / 2 ** 20},
         "full_cycle": {"algorithmic_bytes_per_step": cycle_bytes,
                        "algorithmic_GBps": cycle_bytes / (sec / K) / 1e9,
                        "frac_of_hbm_peak": cycle_bytes / (sec / K) / 1e9 / HBM_PEAK_GBS,
                        "host_wall_ms_per_step": wall / K * 1e3},
-        "roofline": {"bound": "hbm", "kernel": "kvb_step_kernel<128,bf16,1> (kvb_decode)",
+        "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "avg_launch_us": dec_avg_us, "launches": len(dec_us),
                      "algorithmic_bytes_per_launch_avg": sum(dec_bytes) / len(dec_bytes),
-                     "timing": "HIP events around each kvb_decode launch, eager re-run of the same K steps"},
+                     "steps_without_state_update": {
+                         "avg_launch_us": sum(u for u, _ in noflush) / len(noflush),
+                         "achieved": sum(b for _, b in noflush) / (sum(u for u, _ in noflush) * 1e-6) / 1e9},
+                     "timing": "begin/end timestamps of each launch of this kernel (kvb timer = "
+                               "hipExtLaunchKernel events), eager re-run of the same K steps"},
     }
     if not args.no_other_paths:
         res["other_paths"] = time_other_paths(torch, kvb, synth, traffic)

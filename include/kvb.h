@@ -102,6 +102,19 @@ int kvb_decode(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                const float *g, const float *beta, void *out, void *stream);
 
 /*
+ * kvb_decode_flush -- kvb_decode followed by kvb_flush(accepted = NULL, threshold), in one
+ * pass (the paper launches the state update as a second kernel, Sec. 4.2; here a request
+ * whose buffer reaches `threshold` records with this token has its state updated from the
+ * tile the decode step has already read, which saves re-reading it).  Same arguments,
+ * results and error behaviour as the two calls in sequence; state must not be NULL;
+ * threshold 1..cap (threshold 1 is the fused recurrent step: every token is folded at once).
+ */
+int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,
+                     const void *q, const void *k, const void *v,
+                     const float *g, const float *beta, void *out,
+                     int32_t threshold, void *stream);
+
+/*
  * kvb_flush -- the deferred, batched state update (Sec. 3.2, Eq. 5; for GDN the
  * last line of App. A.1 Eq. 16; with `accepted` the accepted-only update of
  * Sec. 3.3 Eq. 8).  For request b: m = fill + (accepted ? accepted[b] : 0); if
@@ -148,6 +161,19 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                const int32_t *len, int32_t Lmax,
                const void *q, const void *k, const void *v,
                const float *g, const float *beta, void *out, void *stream);
+
+/*
+ * Kernel timer (measurement aid, no part of the method).  A timer owns two HIP events.
+ * kvb_timer_arm makes the NEXT kernel that the calling thread launches through this
+ * library record its own begin and end timestamps into them; kvb_timer_read waits for that
+ * kernel and returns its duration.  Timers are host objects: create / destroy allocate and
+ * free them, the only allocation this library ever performs.  Do not arm during stream capture.
+ */
+typedef struct kvb_timer kvb_timer;
+int  kvb_timer_create(kvb_timer **timer);
+int  kvb_timer_arm(kvb_timer *timer);          /* NULL disarms */
+int  kvb_timer_read(kvb_timer *timer, float *microseconds);
+void kvb_timer_destroy(kvb_timer *timer);
 
 /* Static text for a return code (for KVB_EHIP: the last HIP error string of this thread). */
 const char *kvb_strerror(int code);

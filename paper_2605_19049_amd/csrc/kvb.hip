@@ -12,9 +12,14 @@
 // Notation follows App. A.1: gamma_i = exp(G_i), Gamma_il = exp(G_i - G_l).
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "kvb.h"
+
+struct kvb_timer {
+    hipEvent_t start, stop;
+};
 
 namespace {
 
@@ -152,7 +157,8 @@ struct StepArgs {
     float *out;
     int32_t Hk, Hv, cap, T;
     float scale;
-    int32_t advance;  // 1: decode (fill += T after the step); 0: verify (fill untouched)
+    int32_t advance;    // 1: decode (fill += T after the step); 0: verify (fill untouched)
+    int32_t threshold;  // fused decode + flush only: fold the buffer into the state once it holds this many
 };
 
 // ---------------------------------------------------------------------------
@@ -179,7 +185,12 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
-template <int D, typename TIn, int TM, int WREC, bool HAS_STATE>
+//
+// FUSE (decode only): when the append brings the buffer to `threshold` records the same
+// workgroup applies the deferred update S <- gamma_f S0 + sum_{l<=f} Gamma_fl k_l^T u_l to
+// the state tile it already holds in registers and writes it back, which saves the second
+// kernel's re-read of the state.
+template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE>
 __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
 {
     constexpr int LPR = D / 4;       // lanes covering one state row with float4
@@ -192,6 +203,9 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     constexpr int NC = KVB_MAX_CAP + TM;
     // the two smaller window tiers are only launched when the whole buffer fits the window
     constexpr bool TAIL = WREC >= 64;
+    constexpr int LT = 16;                 // records per LDS tile of the fused state update
+    constexpr int EPT = LT * D / NT;
+    static_assert(!FUSE || (TM == 1 && HAS_STATE), "the fused update belongs to kvb_decode with a state");
 
     __shared__ __attribute__((aligned(16))) float sKs[TM][D];  // -gamma_i k_i (state-row weights for accU)
     __shared__ __attribute__((aligned(16))) float sQs[TM][D];  //  gamma_i q_i
@@ -200,6 +214,8 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     __shared__ float cK[TM][NC];     // Gamma_il (k_i.k_l), 0 for l >= f+i
     __shared__ float cQ[TM][NC];     // Gamma_il (q_i.k_l), 0 for l >  f+i
     __shared__ __attribute__((aligned(16))) float red[NW][TM][2][D];
+    __shared__ __attribute__((aligned(16))) float kh[FUSE ? LT : 1][D];  // Gamma_fl k_l tile
+    __shared__ __attribute__((aligned(16))) float uu[FUSE ? LT : 1][D];  // u_l tile
 
     const int tid = threadIdx.x;
     const int lb = logical_block();
@@ -511,6 +527,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     __syncthreads();
 
     // ---- 6. finish the T new rows (forward substitution), write results -----
+    float u_new = 0.0f;
     if (tid < D) {
         float uprev[TM];
 #pragma unroll
@@ -535,6 +552,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                         ao = fmaf(cQ[i][f + j], uprev[j], ao);
                 ao = fmaf(cQ[i][f + i], ui, ao);
                 uprev[i] = ui;
+                u_new = ui;
                 a.out[row * D + tid] = a.scale * ao;
                 a.st.buf_u[(unit * cap + f + i) * D + tid] = ui;
             }
@@ -552,8 +570,58 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         TIn *kw = static_cast<TIn *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f) * D;
         store_raw8(kw + (size_t)nr_i * D + 8 * nr_e, k_raw);
     }
+    int new_fill = f + T;
+    if constexpr (FUSE) {
+        const int m = f + 1;
+        if (m >= a.threshold) {   // uniform over the workgroup (and over the request)
+            const float gam = expf(Gc[0]);
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                sreg[p].x *= gam; sreg[p].y *= gam; sreg[p].z *= gam; sreg[p].w *= gam;
+            }
+            const float *ub = a.st.buf_u + unit * cap * D;
+            for (int l0 = 0; l0 < m; l0 += LT) {
+                __syncthreads();
+                // records before f come back from memory (written by earlier calls); record f
+                // itself is taken from this workgroup's registers
+#pragma unroll
+                for (int x = 0; x < EPT; ++x) {
+                    const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
+                    if (l < f) {
+                        kh[idx / D][e] = expf(Gc[0] - Gbuf[l]) * to_f32(kb[(size_t)l * D + e]);
+                        uu[idx / D][e] = ub[(size_t)l * D + e];
+                    } else if (l > f) {
+                        kh[idx / D][e] = 0.0f;
+                        uu[idx / D][e] = 0.0f;
+                    }
+                }
+                if (f >= l0 && f < l0 + LT) {
+                    if (grp == 0) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            kh[f - l0][8 * sub + e] = k8[e];
+                    }
+                    if (tid < D)
+                        uu[f - l0][tid] = u_new;
+                }
+                __syncthreads();
+                const int nl = min(LT, m - l0);
+                for (int l = 0; l < nl; ++l) {
+                    const float4 u = *reinterpret_cast<const float4 *>(&uu[l][4 * c4]);
+#pragma unroll
+                    for (int p = 0; p < NPASS; ++p)
+                        fma4(sreg[p], kh[l][rg + RPP * p], u);
+                }
+            }
+            float4 *sw = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p)
+                sw[(size_t)(rg + RPP * p) * LPR + c4] = sreg[p];
+            new_fill = 0;
+        }
+    }
     if (a.advance && tid == 0)
-        publish_if_last(&a.st.fill[s], ticket, a.Hv, f + T);
+        publish_if_last(&a.st.fill[s], ticket, a.Hv, new_fill);
 }
 
 // ---------------------------------------------------------------------------
@@ -790,6 +858,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 // host side
 // ---------------------------------------------------------------------------
 thread_local hipError_t g_last_hip_error = hipSuccess;
+thread_local kvb_timer *g_armed = nullptr;
 
 bool aligned(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
 
@@ -844,13 +913,32 @@ int finish_launch()
     return KVB_OK;
 }
 
+// One kernel launch.  If this thread armed a timer, the launch carries its two events so
+// that they hold the kernel's own begin / end timestamps.
+template <typename Args>
+void launch(void (*kernel)(Args), int blocks, hipStream_t stream, const Args &a)
+{
+    kvb_timer *t = g_armed;
+    g_armed = nullptr;
+    if (t)
+        hipExtLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, t->start, t->stop, 0, a);
+    else
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, a);
+}
+
 template <int D, typename TIn, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
+    if constexpr (TM == 1) {
+        if (a.threshold > 0) {
+            launch(kvb_step_kernel<D, TIn, 1, WREC, true, true>, blocks, stream, a);
+            return;
+        }
+    }
     if (a.st.state)
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, TM, WREC, true>), dim3(blocks), dim3(NT), 0, stream, a);
+        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false>, blocks, stream, a);
     else
-        hipLaunchKernelGGL((kvb_step_kernel<D, TIn, TM, WREC, false>), dim3(blocks), dim3(NT), 0, stream, a);
+        launch(kvb_step_kernel<D, TIn, TM, WREC, false, false>, blocks, stream, a);
 }
 
 template <int D, typename TIn, int TM>
@@ -898,7 +986,7 @@ int dispatch(const kvb_shape *sh, F &&f)
 
 int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, int T, const void *q,
                 const void *k, const void *v, const float *g, const float *beta, void *out, void *stream,
-                int advance)
+                int advance, int threshold = 0)
 {
     int rc = check_common(sh, st, slot);
     if (rc != KVB_OK)
@@ -911,7 +999,7 @@ int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, i
     if (sh->B == 0)
         return KVB_OK;
     StepArgs a{dev_store(st), slot, q, k, v, g, beta, static_cast<float *>(out), sh->Hk, sh->Hv, sh->cap, T,
-               sh->scale, advance};
+               sh->scale, advance, threshold};
     const int blocks = sh->B * sh->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(sh, [&]<int D, typename TIn>() { launch_step<D, TIn>(a, blocks, hs); });
@@ -928,6 +1016,17 @@ int kvb_decode(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                const void *v, const float *g, const float *beta, void *out, void *stream)
 {
     return step_common(shape, store, slot, 1, q, k, v, g, beta, out, stream, 1);
+}
+
+int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, const void *q,
+                     const void *k, const void *v, const float *g, const float *beta, void *out,
+                     int32_t threshold, void *stream)
+{
+    if (!shape || !store)
+        return KVB_EINVAL;
+    if (!store->state || threshold < 1 || threshold > shape->cap)
+        return KVB_EINVAL;
+    return step_common(shape, store, slot, 1, q, k, v, g, beta, out, stream, 1, threshold);
 }
 
 int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T, const void *q,
@@ -952,7 +1051,7 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(shape, [&]<int D, typename TIn>() {
-        hipLaunchKernelGGL((kvb_flush_kernel<D, TIn>), dim3(blocks), dim3(NT), 0, hs, a);
+        launch(kvb_flush_kernel<D, TIn>, blocks, hs, a);
     });
     if (rc != KVB_OK)
         return rc;
@@ -980,11 +1079,63 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(shape, [&]<int D, typename TIn>() {
-        hipLaunchKernelGGL((kvb_direct_kernel<D, TIn>), dim3(blocks), dim3(NT), 0, hs, a);
+        launch(kvb_direct_kernel<D, TIn>, blocks, hs, a);
     });
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
+}
+
+int kvb_timer_create(kvb_timer **timer)
+{
+    if (!timer)
+        return KVB_EINVAL;
+    kvb_timer *t = new kvb_timer{nullptr, nullptr};
+    hipError_t e = hipEventCreate(&t->start);
+    if (e == hipSuccess)
+        e = hipEventCreate(&t->stop);
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        if (t->start)
+            (void)hipEventDestroy(t->start);
+        delete t;
+        return KVB_EHIP;
+    }
+    *timer = t;
+    return KVB_OK;
+}
+
+int kvb_timer_arm(kvb_timer *timer)
+{
+    g_armed = timer;
+    return KVB_OK;
+}
+
+int kvb_timer_read(kvb_timer *timer, float *microseconds)
+{
+    if (!timer || !microseconds)
+        return KVB_EINVAL;
+    hipError_t e = hipEventSynchronize(timer->stop);
+    float ms = 0.0f;
+    if (e == hipSuccess)
+        e = hipEventElapsedTime(&ms, timer->start, timer->stop);
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        return KVB_EHIP;
+    }
+    *microseconds = ms * 1000.0f;
+    return KVB_OK;
+}
+
+void kvb_timer_destroy(kvb_timer *timer)
+{
+    if (!timer)
+        return;
+    if (g_armed == timer)
+        g_armed = nullptr;
+    (void)hipEventDestroy(timer->start);
+    (void)hipEventDestroy(timer->stop);
+    delete timer;
 }
 
 const char *kvb_strerror(int code)

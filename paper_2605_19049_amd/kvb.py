@@ -16,7 +16,9 @@ F32, BF16 = 0, 1
 MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 64
 STATUS_OVERFLOW = 1
 
-EXPORTS = ("kvb_decode", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_strerror", "kvb_version")
+EXPORTS = ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_direct",
+           "kvb_timer_create", "kvb_timer_arm", "kvb_timer_read", "kvb_timer_destroy",
+           "kvb_strerror", "kvb_version")
 
 
 class KvbShape(ctypes.Structure):
@@ -53,10 +55,17 @@ def lib():
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         sp, tp = ctypes.POINTER(KvbShape), ctypes.POINTER(KvbStore)
         L.kvb_decode.argtypes = [sp, tp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.kvb_decode_flush.argtypes = [sp, tp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.kvb_flush.argtypes = [sp, tp, vp, vp, i32, vp]
+        L.kvb_timer_create.argtypes = [ctypes.POINTER(vp)]
+        L.kvb_timer_arm.argtypes = [vp]
+        L.kvb_timer_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.kvb_timer_destroy.argtypes = [vp]
+        L.kvb_timer_destroy.restype = None
         L.kvb_verify.argtypes = [sp, tp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.kvb_direct.argtypes = [sp, tp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
-        for name in ("kvb_decode", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_version"):
+        for name in ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_version",
+                     "kvb_timer_create", "kvb_timer_arm", "kvb_timer_read"):
             getattr(L, name).restype = ctypes.c_int
         L.kvb_strerror.argtypes = [ctypes.c_int]
         L.kvb_strerror.restype = ctypes.c_char_p
@@ -108,6 +117,33 @@ def kvb_decode(sh, st, slot, q, k, v, g, beta, out, stream=None, check=True):
     rc = lib().kvb_decode(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), _ptr(q), _ptr(k), _ptr(v),
                           _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
     return _check(rc, "kvb_decode", check)
+
+
+def kvb_decode_flush(sh, st, slot, q, k, v, g, beta, out, threshold, stream=None, check=True):
+    rc = lib().kvb_decode_flush(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), _ptr(q), _ptr(k), _ptr(v),
+                                _ptr(g), _ptr(beta), _ptr(out), threshold, _stream(stream))
+    return _check(rc, "kvb_decode_flush", check)
+
+
+class Timer:
+    """A kvb_timer: arm() before a call, us() after it to get that call's kernel duration."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _check(lib().kvb_timer_create(ctypes.byref(self._h)), "kvb_timer_create", True)
+
+    def arm(self):
+        lib().kvb_timer_arm(self._h)
+
+    def us(self):
+        out = ctypes.c_float()
+        _check(lib().kvb_timer_read(self._h, ctypes.byref(out)), "kvb_timer_read", True)
+        return out.value
+
+    def close(self):
+        if self._h:
+            lib().kvb_timer_destroy(self._h)
+            self._h = ctypes.c_void_p()
 
 
 def kvb_flush(sh, st, slot, accepted, threshold, stream=None, check=True):

@@ -53,6 +53,25 @@ def flush_rw(lay, m):
     return lay.state + m * lay.record, lay.state
 
 
+def decode_flush_rw(lay, fill, threshold):
+    """(read, write) per v-head of one kvb_decode_flush at pre-append fill `fill`: the decode
+    step, plus the state write-back when the append reaches `threshold` (the state and the
+    records are read once, by the decode part)."""
+    rd, wr = decode_rw(lay, fill)
+    if fill + 1 >= threshold:
+        wr += lay.state
+    return rd, wr
+
+
+def fused_cycle_rw(lay, C):
+    """Average (read, write) per token per v-head over one cycle of kvb_decode_flush."""
+    rd = wr = 0.0
+    for j in range(C):
+        a, b = decode_flush_rw(lay, j, C)
+        rd, wr = rd + a, wr + b
+    return rd / C, wr / C
+
+
 def recurrent_rw(lay):
     """(read, write) per v-head of the fused recurrent step (Table 2, row 'Recurrent')."""
     return lay.state + lay.token_in, lay.state + lay.out_bytes * lay.dv

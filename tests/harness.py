@@ -75,6 +75,10 @@ class Layer:
         kvb.kvb_decode(self.shape(B), st, self.slot if slot is None else slot,
                        tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)
 
+    def decode_flush(self, tok, out, threshold, slot=None, B=None):
+        kvb.kvb_decode_flush(self.shape(B), self.ds.c(True), self.slot if slot is None else slot,
+                             tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out, threshold)
+
     def flush(self, threshold, accepted=None, slot=None, B=None):
         kvb.kvb_flush(self.shape(B), self.ds.c(True), self.slot if slot is None else slot, accepted, threshold)
 
@@ -98,7 +102,7 @@ def step_view(dtok, t):
     return {n: x[:, t].contiguous() for n, x in dtok.items()}
 
 
-def run_decode(layer, S0, tok, C, flush_every_step=True, final_flush=True):
+def run_decode(layer, S0, tok, C, flush_every_step=True, final_flush=True, fused=False):
     """Chunkwise decoding of tok (T tokens per request) from committed state S0, flushing
     when the buffer holds C records.  Returns GPU outputs [B,T,Hv,dv], the u records as
     the GPU wrote them [B,T,Hv,dv], and the final state (after a last flush of everything)."""
@@ -112,10 +116,13 @@ def run_decode(layer, S0, tok, C, flush_every_step=True, final_flush=True):
     for t in range(T):
         f_before = int(layer.ds.fill[sl[0]].item())
         o_t = torch.empty((B, layer.Hv, layer.dv), dtype=torch.float32, device=layer.device)
-        layer.decode(step_view(dtok, t), o_t)
+        if fused:      # kvb_decode_flush = decode + flush(threshold=C) in one kernel
+            layer.decode_flush(step_view(dtok, t), o_t, C)
+        else:
+            layer.decode(step_view(dtok, t), o_t)
         out[:, t] = o_t
         u_rec[:, t] = layer.ds.buf_u[sl, :, f_before]
-        if flush_every_step:
+        if flush_every_step and not fused:
             layer.flush(C)
         fills.append(int(layer.ds.fill[sl[0]].item()))
     if final_flush:

@@ -102,6 +102,15 @@ def test_flush_verify_direct_argument_ranges():
     assert kvb.kvb_direct(sh, st, A, None, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
 
 
+def test_decode_flush_argument_ranges():
+    sh = kvb.shape(**GOOD)
+    args = (A, A, A, A, A, A, A)
+    assert kvb.kvb_decode_flush(sh, _store(), *args, 0, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_decode_flush(sh, _store(), *args, 17, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_decode_flush(sh, _store(state=None), *args, 4, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_decode_flush(kvb.shape(**{**GOOD, "B": 0}), _store(), *args, 4, stream=0, check=False) == kvb.OK
+
+
 def test_check_flag_raises():
     sh = kvb.shape(**{**GOOD, "cap": 0})
     with pytest.raises(kvb.KvbError) as e:

@@ -33,8 +33,9 @@ def ragged_warmup(layer, fills, wtok):
 
 
 # --------------------------------------------------------------------------- decode + flush
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("C", [8, 1, 2, 4, 32])
-def test_tiny_fp32_decode_flush(C):
+def test_tiny_fp32_decode_flush(C, fused):
     """Workload 1: all fp32, B=1, 2 heads, d=32, 64-token prefix, 32 steps; any chunk size
     gives the same outputs (chunk-size invariance)."""
     w = synth.WORKLOADS["tiny_fp32"]
@@ -42,10 +43,10 @@ def test_tiny_fp32_decode_flush(C):
     S0 = H.prefix_state(rng, w.B, w.Hk, w.Hv, w.dk, w.dv, "f32", w.prefix)
     tok = synth.token_stream(rng, w.B, w.steps, w.Hk, w.Hv, w.dk, w.dv, "f32")
     lay = H.Layer(w.B, w.Hk, w.Hv, w.dk, w.dv, cap=C, in_dtype="f32")
-    o, u, S, fills = H.run_decode(lay, S0, tok, C)
+    o, u, S, fills = H.run_decode(lay, S0, tok, C, fused=fused)
     o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
     e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
-    say("tiny_fp32 C=%d rel err out/u/state: %.2e %.2e %.2e" % ((C,) + e))
+    say("tiny_fp32 C=%d fused=%s rel err out/u/state: %.2e %.2e %.2e" % ((C, fused) + e))
     assert max(e) < H.TOL["f32"]
     assert fills == [(t + 1) % C for t in range(w.steps)]
     assert not lay.status().any()
@@ -60,30 +61,33 @@ def test_tiny_fp32_decode_flush(C):
     (128, "bf16", 2, 1, 1, 64, 70),
     (128, "bf16", 2, 2, 4, 128, 130),
 ])
-def test_decode_flush_shapes(d, in_dtype, B, Hk, Hv, C, steps):
+@pytest.mark.parametrize("fused", [False, True])
+def test_decode_flush_shapes(d, in_dtype, B, Hk, Hv, C, steps, fused):
     rng = np.random.default_rng(100 + d + C)
     S0 = H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
     tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, in_dtype)
     lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, scale=d ** -0.5)
-    o, u, S, _ = H.run_decode(lay, S0, tok, C)
+    o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=fused)
     o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"],
                                                      scale=d ** -0.5)
     e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
-    say("d=%d %s C=%d rel err out/u/state: %.2e %.2e %.2e" % ((d, in_dtype, C) + e))
+    say("d=%d %s C=%d fused=%s rel err out/u/state: %.2e %.2e %.2e" % ((d, in_dtype, C, fused) + e))
     assert max(e) < H.TOL[in_dtype]
 
 
-def test_qwen3next_decode_full():
-    """Workload 2 at full size: B=64, 16/32 heads, d=128, bf16, C=16, 256 steps."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_qwen3next_decode_full(fused):
+    """Workload 2 at full size: B=64, 16/32 heads, d=128, bf16, C=16, 256 steps; as
+    kvb_decode + kvb_flush and as the single-kernel kvb_decode_flush."""
     w = synth.WORKLOADS["qwen3next_decode"]
     rng = np.random.default_rng(w.seed)
     S0 = H.prefix_state(rng, w.B, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype, w.prefix)
     tok = synth.token_stream(rng, w.B, w.steps, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype)
     lay = H.Layer(w.B, w.Hk, w.Hv, w.dk, w.dv, cap=w.cap, in_dtype=w.in_dtype)
-    o, u, S, fills = H.run_decode(lay, S0, tok, w.C)
+    o, u, S, fills = H.run_decode(lay, S0, tok, w.C, fused=fused)
     o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
     e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
-    say("qwen3next_decode rel err out/u/state: %.2e %.2e %.2e" % e)
+    say("qwen3next_decode fused=%s rel err out/u/state: %.2e %.2e %.2e" % ((fused,) + e))
     assert max(e) < H.TOL["bf16"]
     assert fills == [(t + 1) % w.C for t in range(w.steps)]
 
@@ -237,8 +241,11 @@ def test_mixed_fill_batch_reduced():
         out = torch.empty((B, steps, Hv, d), dtype=torch.float32, device="cuda")
         for t in range(steps):
             o_t = torch.empty((B, Hv, d), dtype=torch.float32, device="cuda")
-            lay.decode(H.step_view(dt, t), o_t)
-            lay.flush(C)
+            if layer_i % 2:
+                lay.decode_flush(H.step_view(dt, t), o_t, C)
+            else:
+                lay.decode(H.step_view(dt, t), o_t)
+                lay.flush(C)
             out[:, t] = o_t
         torch.cuda.synchronize()
         assert np.array_equal(lay.fill(), (fills + steps) % C)
@@ -427,3 +434,20 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(got, ref), "replay %d differs from eager" % rep
         loop()                       # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_kernel_timer_reports_the_armed_launch():
+    rng = np.random.default_rng(77)
+    lay = _small_layer(cap=4)
+    lay.set_state(synth.random_state(rng, 3, 2, 128, 128))
+    tok = H.upload_tokens(synth.token_stream(rng, 3, 2, 1, 2, 128, 128, "bf16"), "bf16")
+    out = torch.empty((3, 2, 128), dtype=torch.float32, device="cuda")
+    t = kvb.Timer()
+    t.arm()
+    lay.decode(H.step_view(tok, 0), out)
+    lay.decode(H.step_view(tok, 1), out)      # not timed: the arm covers one launch
+    us = t.us()
+    t.close()
+    torch.cuda.synchronize()
+    assert 0.5 < us < 5000.0
+    assert np.array_equal(lay.fill(), [2, 2, 2])
