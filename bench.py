@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--step", choices=["fused", "split"], default="fused")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the K timed steps are one HIP graph launch; eager: one launch per kernel")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="override the workload's batch size (e.g. 512: 1 GiB of state, beyond the last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-paths", action="store_true")
     return ap.parse_args()
@@ -38,7 +40,7 @@ def parse():
 class DecodeJob:
     """Device-resident workload: store, a ring of token inputs, pre-marshalled calls."""
 
-    def __init__(self, w, ring=64, fused=True):
+    def __init__(self, w, ring=32, fused=True):
         import numpy as np
         import torch
         from paper_2605_19049_amd import kvb, synth
@@ -195,6 +197,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     kvb.lib()   # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
+    if args.batch:
+        import dataclasses
+        w = dataclasses.replace(w, B=args.batch, name="%s(B=%d)" % (w.name, args.batch))
     K, W = args.steps, args.warmup
 
     fused = args.step == "fused"

@@ -50,6 +50,13 @@ extern "C" {
 #define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
 #define KVB_MAX_DIRECT_LEN  64 /* largest Lmax of kvb_direct in this build                      */
 
+/* kvb_store.flags: how the state should travel through the caches.  With neither bit the
+ * library streams (non-temporal loads) when one call touches more state than the 256 MB
+ * last-level cache holds.  A model with many GDN layers should set KVB_STORE_STREAM: each
+ * layer's state is next read one token later, after every other layer's has passed through. */
+#define KVB_STORE_STREAM   1
+#define KVB_STORE_RESIDENT 2
+
 /* bit set in status[slot] when a call would have overrun that request's buffer */
 #define KVB_STATUS_OVERFLOW 1
 
@@ -78,6 +85,7 @@ typedef struct kvb_store {
     int32_t *status;  /* device [n_slots] sticky KVB_STATUS_* bits, or NULL                 */
     int32_t  n_slots; /* slots in the arrays above; requests whose slot is outside
                          0..n_slots-1 are skipped                                           */
+    int32_t  flags;   /* KVB_STORE_* hints, 0 = let the library decide                      */
 } kvb_store;
 
 /*

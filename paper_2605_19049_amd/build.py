@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "-std=c++20", "-O3", "--offload-arch=gfx950",
     # hipcc must not emit packed-fp32 VALU instructions on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep the single-lane ticket atomics as written: the wave-aggregating rewrite reads
+    # the result back at once, which would make the wave wait for its whole state tile
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-shared", "-fPIC", "-I" + os.path.join(ROOT, "include"),
 ]
 
@@ -22,7 +25,7 @@ HIPCC_FLAGS = [
 def build_lib(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".%d.tmp" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", tmp, SRC]
+    cmd = [hipcc] + HIPCC_FLAGS + os.environ.get("KVB_EXTRA_HIPCC_FLAGS", "").split() + ["-o", tmp, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

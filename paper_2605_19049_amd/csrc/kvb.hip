@@ -85,6 +85,21 @@ __device__ __forceinline__ void unpack8(const Raw8<bf16_t> &r, float (&o)[8])
     o[6] = __uint_as_float(r.w.w << 16); o[7] = __uint_as_float(r.w.w & 0xFFFF0000u);
 }
 
+// One 16-byte piece of the state tile.  STREAM: non-temporal load, for a state that will
+// not be read again before the last-level cache has turned over (measured on MI355X:
+// +14% at 1 GiB of state per call, -5% at 128 MiB, which the 256 MB cache keeps).
+template <bool STREAM>
+__device__ __forceinline__ float4 load_state4(const float4 *p)
+{
+    if constexpr (STREAM) {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+        return make_float4(t.x, t.y, t.z, t.w);
+    } else {
+        return *p;
+    }
+}
+
 __device__ __forceinline__ void fma4(float4 &acc, float c, const float4 &x)
 {
     acc.x = fmaf(c, x.x, acc.x);
@@ -111,6 +126,9 @@ __device__ __forceinline__ int take_ticket(int32_t *word)
 }
 __device__ __forceinline__ void publish_if_last(int32_t *word, int ticket, int nwg, int new_fill)
 {
+    // Opaque to the optimiser: otherwise the shift below is hoisted next to the atomic and
+    // the wave waits there for the ticket (and for every load it issued before it).
+    asm volatile("" : "+v"(ticket));
     if ((ticket >> 16) == nwg - 1)
         __hip_atomic_store(word, new_fill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -159,6 +177,7 @@ struct StepArgs {
     float scale;
     int32_t advance;    // 1: decode (fill += T after the step); 0: verify (fill untouched)
     int32_t threshold;  // fused decode + flush only: fold the buffer into the state once it holds this many
+    int32_t stream_state;  // non-temporal state loads
 };
 
 // ---------------------------------------------------------------------------
@@ -190,7 +209,7 @@ __device__ __forceinline__ float group_sum(float x)
 // workgroup applies the deferred update S <- gamma_f S0 + sum_{l<=f} Gamma_fl k_l^T u_l to
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
-template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE>
+template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM>
 __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
 {
     constexpr int LPR = D / 4;       // lanes covering one state row with float4
@@ -297,13 +316,17 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + tid % D];
 
     // ---- 2. the state tile goes in flight ---------------------------------
+    // (scheduling fences: the instruction scheduler must not move a small load below
+    // the state loads, or a state load above them)
+    __builtin_amdgcn_sched_barrier(0);
     float4 sreg[NPASS];
     if constexpr (HAS_STATE) {
         const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
 #pragma unroll
         for (int p = 0; p < NPASS; ++p)
-            sreg[p] = sp[(size_t)(rg + RPP * p) * LPR + c4];
+            sreg[p] = load_state4<STREAM>(sp + (size_t)(rg + RPP * p) * LPR + c4);
     }
+    __builtin_amdgcn_sched_barrier(0);
     // youngest memory operation of the wave: nothing waits for it before the very end
     int ticket = 0;
     if (a.advance && tid == 0)
@@ -855,6 +878,213 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// kvb_direct for bf16 inputs and d = 128: the two Gram matrices K K^T and Q K^T are dense
+// contractions over dk = 128 of operands that are bf16 to begin with, so they go on the
+// matrix cores (v_mfma_f32_16x16x32_bf16, exact products, fp32 accumulate).  The unit
+// lower-triangular solve for U and the product (Q K^T . Gamma) U have fp32 operands and a
+// sequential dependence over rows; they run on the vector ALUs, two lanes per dv column.
+//
+// MFMA operand layout used below (16x16x32): lane l supplies row l%16 of A (resp. column
+// l%16 of B) at k = 8*(l/16) .. +7; it receives C[4*(l/16) + v][l%16], v = 0..3.
+// ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// Row I of the solve, for the lane pair that owns dv column j (fully unrolled over I so
+// that the delta values stay in registers).  Lane parity p owns rows l with (l / 4) % 2 == p,
+// kept in ureg[4 * (l / 8) + l % 4]; a row's register holds v_l until u_l replaces it.
+template <int I, int LM, int D>
+__device__ __forceinline__ void direct_row(const float (&cK)[LM][LM], const float (&cQ)[LM][LM],
+                                           const float (&sB)[LM], const float (&sD)[LM], float (&ureg)[LM / 2],
+                                           int p, float scale, float *out_row, float *u_row)
+{
+    constexpr int NB = (I + 7) / 8;   // blocks of 8 earlier rows that touch rows < I
+    float acck = 0.0f, accq = 0.0f;
+#pragma unroll
+    for (int m = 0; m < NB; ++m) {
+        // coefficients of rows >= I are zero, so a partly covered block needs no masking
+        const float4 ck = *reinterpret_cast<const float4 *>(&cK[I][8 * m + 4 * p]);
+        const float4 cq = *reinterpret_cast<const float4 *>(&cQ[I][8 * m + 4 * p]);
+        acck = fmaf(ck.x, ureg[4 * m + 0], acck); accq = fmaf(cq.x, ureg[4 * m + 0], accq);
+        acck = fmaf(ck.y, ureg[4 * m + 1], acck); accq = fmaf(cq.y, ureg[4 * m + 1], accq);
+        acck = fmaf(ck.z, ureg[4 * m + 2], acck); accq = fmaf(cq.z, ureg[4 * m + 2], accq);
+        acck = fmaf(ck.w, ureg[4 * m + 3], acck); accq = fmaf(cq.w, ureg[4 * m + 3], accq);
+    }
+    acck += __shfl_xor(acck, 1);
+    accq += __shfl_xor(accq, 1);
+    constexpr int R = 4 * (I / 8) + I % 4;      // register of row I in its owner lane
+    const float ui = sB[I] * (ureg[R] - acck);
+    const float o = fmaf(sD[I], ui, accq);
+    if (p == (I / 4) % 2) {
+        ureg[R] = ui;
+        *out_row = scale * o;
+        *u_row = ui;
+    }
+}
+
+template <int I0, int LM, int D>
+__device__ __forceinline__ void direct_rows8(const float (&cK)[LM][LM], const float (&cQ)[LM][LM],
+                                             const float (&sB)[LM], const float (&sD)[LM], float (&ureg)[LM / 2],
+                                             int p, float scale, int L, float *out0, size_t out_stride, float *u0)
+{
+    // rows I0 .. I0+7; L is uniform over the workgroup
+#define KVB_ROW(X)                                                                                          \
+    if (I0 + X < L)                                                                                         \
+        direct_row<I0 + X, LM, D>(cK, cQ, sB, sD, ureg, p, scale, out0 + (size_t)(I0 + X) * out_stride,      \
+                                  u0 + (size_t)(I0 + X) * D);
+    KVB_ROW(0) KVB_ROW(1) KVB_ROW(2) KVB_ROW(3) KVB_ROW(4) KVB_ROW(5) KVB_ROW(6) KVB_ROW(7)
+#undef KVB_ROW
+}
+
+__global__ __launch_bounds__(NT) void kvb_direct_mfma_kernel(const DirectArgs a)
+{
+    constexpr int D = 128;
+    constexpr int LM = KVB_MAX_DIRECT_LEN;
+    static_assert(LM == 64, "tile table below is for 4 x 4 tiles of 16");
+    __shared__ __attribute__((aligned(16))) float cK[LM][LM];  // Gamma_il (k_i.k_l) for l < i, else 0
+    __shared__ __attribute__((aligned(16))) float cQ[LM][LM];  // Gamma_il (q_i.k_l) for l < i, else 0
+    __shared__ float sG[LM];
+    __shared__ float sB[LM];
+    __shared__ float sD[LM];                                   // q_i.k_i (the l = i term of the output)
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int hk = h / r;
+    const int Lmax = a.Lmax;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    int L = a.len[b];
+    if (L < 0 || L > Lmax) {
+        L = Lmax;
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+    }
+    if (L == 0) {
+        if (h == 0 && tid == 0)
+            a.st.fill[s] = 0;
+        return;
+    }
+    const size_t unit = (size_t)s * a.Hv + h;
+    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
+    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
+    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+
+    // this lane's v values (rows past the context are clamped to a valid row and never used)
+    const int j = tid / 2, p = tid % 2;
+    bf16_t v_raw[LM / 2];
+#pragma unroll
+    for (int n = 0; n < LM / 2; ++n) {
+        const int l = min(8 * (n / 4) + 4 * p + n % 4, L - 1);
+        v_raw[n] = vin[(((size_t)b * Lmax + l) * a.Hv + h) * D + j];
+    }
+
+    // cumulative log decay (inclusive scan over the wave) and beta
+    if (wave == 0) {
+        float gv = lane < L ? a.g[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_up(gv, off);
+            if (lane >= off)
+                gv += t;
+        }
+        sG[lane] = gv;
+        sB[lane] = lane < L ? a.beta[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+    }
+
+    // ---- Gram tiles on the matrix cores --------------------------------------
+    const int ntile = (L + 15) / 16;
+    f32x4_t accK[3], accQ[3];
+    int tile_i[3], tile_j[3];
+    {
+        // lower-triangular 16x16 tiles of the 64x64 matrices, dealt to the 4 waves
+        constexpr int TI[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
+        constexpr int TJ[10] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+#pragma unroll
+        for (int n = 0; n < 3; ++n) {
+            const int t = wave + 4 * n;
+            tile_i[n] = t < 10 ? TI[t] : 99;
+            tile_j[n] = t < 10 ? TJ[t] : 0;
+            accK[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            accQ[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (tile_i[n] < ntile) {   // uniform over the wave
+                const int ri = min(16 * tile_i[n] + lane % 16, L - 1);
+                const int rj = min(16 * tile_j[n] + lane % 16, L - 1);
+                const size_t oi = (((size_t)b * Lmax + ri) * a.Hk + hk) * D + 8 * (lane / 16);
+                const size_t oj = (((size_t)b * Lmax + rj) * a.Hk + hk) * D + 8 * (lane / 16);
+                uint4 ak[D / 32], aq[D / 32], bk[D / 32];
+#pragma unroll
+                for (int st = 0; st < D / 32; ++st) {
+                    ak[st] = *reinterpret_cast<const uint4 *>(kin + oi + 32 * st);
+                    aq[st] = *reinterpret_cast<const uint4 *>(qin + oi + 32 * st);
+                    bk[st] = *reinterpret_cast<const uint4 *>(kin + oj + 32 * st);
+                }
+#pragma unroll
+                for (int st = 0; st < D / 32; ++st) {
+                    accK[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ak[st]),
+                                                                      __builtin_bit_cast(bf16x8_t, bk[st]), accK[n], 0, 0, 0);
+                    accQ[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq[st]),
+                                                                      __builtin_bit_cast(bf16x8_t, bk[st]), accQ[n], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();   // sG visible
+#pragma unroll
+    for (int n = 0; n < 3; ++n) {
+        if (tile_i[n] < ntile) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * tile_i[n] + 4 * (lane / 16) + v;
+                const int jj = 16 * tile_j[n] + lane % 16;
+                const float w = (i < L && jj < i) ? expf(sG[i] - sG[jj]) : 0.0f;
+                cK[i][jj] = w * accK[n][v];
+                cQ[i][jj] = w * accQ[n][v];
+                if (i == jj)
+                    sD[i] = accQ[n][v];
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- the solve and the outputs, row after row, delta values in registers ----
+    {
+        float ureg[LM / 2];
+#pragma unroll
+        for (int n = 0; n < LM / 2; ++n)
+            ureg[n] = to_f32(v_raw[n]);
+        float *out0 = a.out + (((size_t)b * Lmax) * a.Hv + h) * D + j;
+        const size_t ostride = (size_t)a.Hv * D;
+        float *u0 = a.st.buf_u + unit * a.cap * D + j;
+        direct_rows8<0, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 8) direct_rows8<8, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 16) direct_rows8<16, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 24) direct_rows8<24, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 32) direct_rows8<32, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 40) direct_rows8<40, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 48) direct_rows8<48, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+        if (L > 56) direct_rows8<56, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+    }
+
+    if (tid < L)
+        a.st.buf_G[unit * a.cap + tid] = sG[tid];
+    if (h % r == 0) {
+        bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * a.cap * D;
+        for (int c = tid; c < L * (D / 8); c += NT) {
+            const int i = c / (D / 8), e8 = c % (D / 8);
+            *reinterpret_cast<uint4 *>(kb + (size_t)i * D + 8 * e8) =
+                *reinterpret_cast<const uint4 *>(kin + (((size_t)b * Lmax + i) * a.Hk + hk) * D + 8 * e8);
+        }
+    }
+    if (h == 0 && tid == 0)
+        a.st.fill[s] = L;
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 thread_local hipError_t g_last_hip_error = hipSuccess;
@@ -898,6 +1128,18 @@ int check_tokens(const void *q, const void *k, const void *v, const float *g, co
     return KVB_OK;
 }
 
+// Whether the state should be streamed past the caches: the caller's hint, else by this
+// call's own state footprint against the 256 MB last-level cache.
+bool stream_state(const kvb_shape *sh, const kvb_store *st)
+{
+    if (st->flags & KVB_STORE_STREAM)
+        return true;
+    if (st->flags & KVB_STORE_RESIDENT)
+        return false;
+    const double bytes = 4.0 * sh->B * sh->Hv * sh->dk * sh->dv;
+    return bytes > 384.0 * 1024 * 1024;
+}
+
 Store dev_store(const kvb_store *st)
 {
     return Store{st->state, st->buf_k, st->buf_u, st->buf_G, st->fill, st->status, st->n_slots};
@@ -929,16 +1171,24 @@ void launch(void (*kernel)(Args), int blocks, hipStream_t stream, const Args &a)
 template <int D, typename TIn, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
+    // (a branch inside the kernel around the state loads would make the compiler's wait
+    // counters conservative at the join, so these are compile-time variants)
+    const bool st = a.stream_state != 0;
     if constexpr (TM == 1) {
         if (a.threshold > 0) {
-            launch(kvb_step_kernel<D, TIn, 1, WREC, true, true>, blocks, stream, a);
+            if (st)
+                launch(kvb_step_kernel<D, TIn, 1, WREC, true, true, true>, blocks, stream, a);
+            else
+                launch(kvb_step_kernel<D, TIn, 1, WREC, true, true, false>, blocks, stream, a);
             return;
         }
     }
-    if (a.st.state)
-        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false>, blocks, stream, a);
+    if (!a.st.state)
+        launch(kvb_step_kernel<D, TIn, TM, WREC, false, false, false>, blocks, stream, a);
+    else if (st)
+        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false, true>, blocks, stream, a);
     else
-        launch(kvb_step_kernel<D, TIn, TM, WREC, false, false>, blocks, stream, a);
+        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false, false>, blocks, stream, a);
 }
 
 template <int D, typename TIn, int TM>
@@ -999,7 +1249,7 @@ int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, i
     if (sh->B == 0)
         return KVB_OK;
     StepArgs a{dev_store(st), slot, q, k, v, g, beta, static_cast<float *>(out), sh->Hk, sh->Hv, sh->cap, T,
-               sh->scale, advance, threshold};
+               sh->scale, advance, threshold, stream_state(sh, st) ? 1 : 0};
     const int blocks = sh->B * sh->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(sh, [&]<int D, typename TIn>() { launch_step<D, TIn>(a, blocks, hs); });
@@ -1078,6 +1328,10 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                  shape->cap, Lmax, shape->scale};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (shape->dk == 128 && shape->in_dtype == KVB_BF16) {
+        launch(kvb_direct_mfma_kernel, blocks, hs, a);
+        return finish_launch();
+    }
     rc = dispatch(shape, [&]<int D, typename TIn>() {
         launch(kvb_direct_kernel<D, TIn>, blocks, hs, a);
     });

@@ -15,6 +15,7 @@ OK, EINVAL, EUNSUPPORTED, EHIP = 0, -1, -2, -3
 F32, BF16 = 0, 1
 MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 64
 STATUS_OVERFLOW = 1
+STORE_STREAM, STORE_RESIDENT = 1, 2
 
 EXPORTS = ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_direct",
            "kvb_timer_create", "kvb_timer_arm", "kvb_timer_read", "kvb_timer_destroy",
@@ -31,7 +32,7 @@ class KvbShape(ctypes.Structure):
 class KvbStore(ctypes.Structure):
     _fields_ = [("state", ctypes.c_void_p), ("buf_k", ctypes.c_void_p), ("buf_u", ctypes.c_void_p),
                 ("buf_G", ctypes.c_void_p), ("fill", ctypes.c_void_p), ("status", ctypes.c_void_p),
-                ("n_slots", ctypes.c_int32)]
+                ("n_slots", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class KvbError(RuntimeError):
@@ -95,8 +96,8 @@ def shape(B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, out_dtype=F32):
     return KvbShape(B, Hk, Hv, dk, dv, cap, in_dtype, out_dtype, scale)
 
 
-def store(state, buf_k, buf_u, buf_G, fill, status, n_slots):
-    return KvbStore(_ptr(state), _ptr(buf_k), _ptr(buf_u), _ptr(buf_G), _ptr(fill), _ptr(status), n_slots)
+def store(state, buf_k, buf_u, buf_G, fill, status, n_slots, flags=0):
+    return KvbStore(_ptr(state), _ptr(buf_k), _ptr(buf_u), _ptr(buf_G), _ptr(fill), _ptr(status), n_slots, flags)
 
 
 def strerror(code):
@@ -204,6 +205,6 @@ class DeviceStore:
         self.fill = torch.zeros((n_slots,), dtype=torch.int32, device=device)
         self.status = torch.zeros((n_slots,), dtype=torch.int32, device=device)
 
-    def c(self, with_state=True):
+    def c(self, with_state=True, flags=0):
         return store(self.state if with_state else None, self.buf_k, self.buf_u, self.buf_G, self.fill,
-                     self.status, self.n_slots)
+                     self.status, self.n_slots, flags)

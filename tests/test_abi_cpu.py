@@ -35,7 +35,8 @@ def test_version_and_error_strings():
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(kvb.KvbShape) == 9 * 4
-    assert kvb.KvbStore.n_slots.offset == 6 * 8
+    assert kvb.KvbStore.n_slots.offset == 6 * 8 and kvb.KvbStore.flags.offset == 6 * 8 + 4
+    assert ctypes.sizeof(kvb.KvbStore) == 7 * 8
 
 
 A = 0x1000  # a fake, well-aligned "device address": validation must fail before it is used
