@@ -32,6 +32,8 @@ def parse():
                     help="graph: the K timed steps are one HIP graph launch; eager: one launch per kernel")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (e.g. 512: 1 GiB of state, beyond the last-level cache)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-paths", action="store_true")
     return ap.parse_args()
@@ -169,6 +171,21 @@ def time_other_paths(torch, kvb, synth, traffic, reps=20):
     return res
 
 
+def measured_traffic(workload, fused):
+    """HBM bytes per launch of the dominant kernel as the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    counters measured them (summary under profiles/); None for other configurations."""
+    if workload != "qwen3next_decode" or not fused:
+        return None
+    path = os.path.join(ROOT, "profiles", "kvb_decode_flush_qwen3next_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, tok_np, steps=512):
     """The fp64 oracle, as it stands, on the host cores: same shapes, same token values."""
     import numpy as np
@@ -202,6 +219,14 @@ def main():
         w = dataclasses.replace(w, B=args.batch, name="%s(B=%d)" % (w.name, args.batch))
     K, W = args.steps, args.warmup
 
+    if args.copy_calibration:
+        # a plain copy kernel of known size: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     fused = args.step == "fused"
     job = DecodeJob(w, fused=fused)
     # untimed: build a real committed state by decoding a prompt-sized prefix, then W warm-up steps
@@ -277,7 +302,7 @@ def main():
                        "host_wall_ms_per_step": wall / K * 1e3},
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, fused),
                      "avg_launch_us": dec_avg_us, "launches": len(dec_us),
                      "algorithmic_bytes_per_launch_avg": sum(dec_bytes) / len(dec_bytes),
                      "steps_without_state_update": {
