@@ -2,8 +2,8 @@
  * kvb -- KVBuffer-style Gated DeltaNet decoding for AMD MI355X (gfx950).
  *
  * C ABI of the library.  Every pointer marked "device" is device memory owned
- * by the caller; the library never allocates, frees or synchronises, keeps no
- * global state, and enqueues all work on the caller's HIP stream (`stream` is a
+ * by the caller; the compute calls never allocate, free or synchronise, keep no
+ * global state, and enqueue all work on the caller's HIP stream (`stream` is a
  * hipStream_t passed as void*; NULL = the default stream).  The two structs are
  * host memory and are read only during the call.
  *
@@ -89,7 +89,7 @@ typedef struct kvb_store {
 } kvb_store;
 
 /*
- * All four calls take `slot`: device int32 [B], the store slot of request b.
+ * All compute calls take `slot`: device int32 [B], the store slot of request b.
  * A slot must not appear twice in one call.  state, buf_k, buf_u, q, k, v and
  * out must be 16-byte aligned; the int32 / float vectors 4-byte aligned.
  */
@@ -127,9 +127,9 @@ int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32
  * last line of App. A.1 Eq. 16; with `accepted` the accepted-only update of
  * Sec. 3.3 Eq. 8).  For request b: m = fill + (accepted ? accepted[b] : 0); if
  * m >= threshold and m > 0:  S <- exp(G_{m-1}) S + sum_l exp(G_{m-1} - G_l) k_l^T u_l
- * and fill = 0; otherwise fill = m and the state is untouched.  The only call
- * that writes `state` (which must not be NULL).  On a zeroed state this is the
- * KV-only -> state transition of Sec. 3.4.
+ * and fill = 0; otherwise fill = m and the state is untouched.  Besides
+ * kvb_decode_flush the only call that writes `state` (which must not be NULL).
+ * On a zeroed state this is the KV-only -> state transition of Sec. 3.4.
  *   accepted  device int32 [B] (each 0..T of the preceding kvb_verify) or NULL
  *   threshold 1..cap; 1 flushes every non-empty buffer
  * m > cap sets KVB_STATUS_OVERFLOW and is treated as cap.

@@ -323,8 +323,10 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     if constexpr (HAS_STATE) {
         const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p)
+        for (int p = 0; p < NPASS; ++p) {
             sreg[p] = load_state4<STREAM>(sp + (size_t)(rg + RPP * p) * LPR + c4);
+            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     // youngest memory operation of the wave: nothing waits for it before the very end
@@ -1085,6 +1087,267 @@ __global__ __launch_bounds__(NT) void kvb_direct_mfma_kernel(const DirectArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// kvb_verify for bf16 inputs and d = 128, on the matrix cores.
+//
+// With T drafts the step is a pair of small dense contractions (Sec. 3.3, Eq. 7; Eq. 15):
+//   stage 1   C1[m][l] = W[m] . k_l        W = [k_0..k_7 ; q_0..q_7] (16 x dk, bf16),
+//             l over the buffered and the new keys  -> v_mfma_f32_16x16x32_bf16
+//   stage 2   acc[m][:] = sum_rows sW[row][m] S0[row][:] + sum_{l<f} cW[l][m] u_l[:]
+//             (16 x (dk + f)) . ((dk + f) x dv), fp32 operands -> v_mfma_f32_16x16x4_f32
+// where sW[row][m] = -gamma_i k_i[row] (m = i) or gamma_i q_i[row] (m = 8 + i) and
+// cW[l][m] = -/+ Gamma_il C1[m][l].  The cost of stage 2 does not depend on T <= 8.
+// Each wave owns 32 dv columns for all rows, so no reduction across waves is needed; a
+// lane loads 2 adjacent columns of 4 consecutive rows' worth of lanes (16 lanes x 8 B =
+// one 128-byte line per row).  MFMA layouts: see kvb_direct_mfma_kernel; for 16x16x4 fp32
+// lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives C[4*(l/16)+v][l%16].
+// ---------------------------------------------------------------------------
+template <int WREC, bool HAS_STATE, bool STREAM>
+__global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
+{
+    constexpr int D = 128;
+    constexpr int TMX = KVB_MAX_DRAFTS;                       // 8
+    constexpr int NTILE = (KVB_MAX_CAP + TMX + 15) / 16;      // key tiles of 16 (9)
+    constexpr int NTW = ((WREC + TMX + 15) / 16 + NW - 1) / NW;  // tiles per wave held in registers
+    constexpr int WQ = WREC / 4;                              // record quads held in registers
+    constexpr bool TAIL = WREC >= 64;
+    static_assert(TMX == 8, "row m of W is draft m % 8");
+
+    __shared__ __attribute__((aligned(16))) float sW[D][16];
+    __shared__ __attribute__((aligned(16))) float cW[NTILE * 16][16];
+    __shared__ __attribute__((aligned(16))) float fin[16][D];
+    __shared__ float sGc[NW][TMX];
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int hk = h / r;
+    const int T = a.T;
+    const int cap = a.cap;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    const int f = a.st.fill[s] & FILL_MASK;
+    if (f + T > cap) {
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+        return;
+    }
+    const size_t unit = (size_t)s * a.Hv + h;
+    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
+    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
+    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const float *Gbuf = a.st.buf_G + unit * cap;
+    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
+    const float *ub = a.st.buf_u + unit * cap * D;
+
+    const int lm = lane % 16, lq = lane / 16;   // MFMA row/column index and k index of this lane
+    const int nrec = f + T;
+    const int ntile = (nrec + 15) / 16;
+
+    // per-draft scalars.  Cumulative log decay of draft lane % 8, by a segmented scan, and a
+    // per-wave LDS table of all of them (looked up by draft index later; a register array
+    // indexed at run time would live in scratch memory, whose loads share the counter of the
+    // state loads).
+    float bet[TMX];
+#pragma unroll
+    for (int i = 0; i < TMX; ++i)
+        bet[i] = i < T ? a.beta[((size_t)b * T + i) * a.Hv + h] : 0.0f;
+    float Gmine = lane % 8 < T ? a.g[((size_t)b * T + lane % 8) * a.Hv + h] : 0.0f;
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+        const float t = __shfl_up(Gmine, off, 8);
+        if (lane % 8 >= off)
+            Gmine += t;
+    }
+    Gmine += f > 0 ? Gbuf[f - 1] : 0.0f;
+    if (lane < 8)
+        sGc[wave][lane] = Gmine;
+
+    // ---- 1. small loads: raw bits, clamped addresses, no branches -----------
+    // row lm of W (draft lm % 8; k for lm < 8, q above), k-chunk lq of each 32-wide step
+    const int wi = min(lm % 8, T - 1);
+    const bf16_t *wrow = (lm < 8 ? kin : qin) + (((size_t)b * T + wi) * a.Hk + hk) * D + 8 * lq;
+    uint4 wa[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+        wa[st] = *reinterpret_cast<const uint4 *>(wrow + 32 * st);
+    // keys of this wave's tiles (buffered first, then the new ones)
+    uint4 kt[NTW][4];
+    float Gn[NTW];
+#pragma unroll
+    for (int x = 0; x < NTW; ++x) {
+        const int n = 16 * (wave + NW * x) + lm;
+        const bf16_t *kp = n < f ? kb + (size_t)n * D
+                                 : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
+        Gn[x] = Gbuf[n < f ? n : 0];
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+            kt[x][st] = *reinterpret_cast<const uint4 *>(kp + 8 * lq + 32 * st);
+    }
+    // buffered delta values: quad sq = records 4 sq .. 4 sq + 3, this lane: record 4 sq + lq,
+    // columns 32 wave + 2 lm, + 1
+    const int col2 = 32 * wave + 2 * lm;
+    float2 uq[WQ];
+#pragma unroll
+    for (int sq = 0; sq < WQ; ++sq) {
+        const int l = 4 * sq + lq;
+        uq[sq] = *reinterpret_cast<const float2 *>(ub + (size_t)(l < f ? l : 0) * D + col2);
+    }
+    // v of this wave's columns (used by lanes 0..31 in the last stage)
+    const int colf = 32 * wave + lane % 32;
+    bf16_t v_raw[TMX];
+#pragma unroll
+    for (int i = 0; i < TMX; ++i)
+        v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + colf];
+
+    // ---- 2. the state: rows 4 st + lq, the wave's 32 columns -----------------
+    __builtin_amdgcn_sched_barrier(0);
+    float2 sreg[D / 4];
+    if constexpr (HAS_STATE) {
+        const float *sp = a.st.state + unit * D * D + col2;
+#pragma unroll
+        for (int st = 0; st < D / 4; ++st) {
+            const float2 *p = reinterpret_cast<const float2 *>(sp + (size_t)(4 * st + lq) * D);
+            if constexpr (STREAM) {
+                typedef float v2f __attribute__((ext_vector_type(2)));
+                const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+                sreg[st] = make_float2(t.x, t.y);
+            } else {
+                sreg[st] = *p;
+            }
+            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- 3. stage 1: weights of the state rows, decayed dot products ----------
+    {
+        // the chunk this lane holds for step == wave covers state rows 32 wave + 8 lq .. + 7
+        float x[8];
+        unpack8(Raw8<bf16_t>{wa[0]}, x);
+#pragma unroll
+        for (int st = 1; st < 4; ++st) {
+            float y[8];
+            unpack8(Raw8<bf16_t>{wa[st]}, y);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                x[e] = wave == st ? y[e] : x[e];
+        }
+        const bool live = lm % 8 < T;
+        const float gam = live ? expf(Gmine) : 0.0f;   // lm % 8 == lane % 8
+        const float sg = lm < 8 ? -gam : gam;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            sW[32 * wave + 8 * lq + e][lm] = sg * x[e];
+    }
+    auto key_tile = [&](int tile, const uint4(&kk)[4], float Gx) {
+        f32x4_t c1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[st]),
+                                                         __builtin_bit_cast(bf16x8_t, kk[st]), c1, 0, 0, 0);
+        // this lane: rows m = 4 lq + v of W against key n
+        const int n = 16 * tile + lm;
+        const float Gkey = n < f ? Gx : sGc[wave][min(max(n - f, 0), TMX - 1)];
+        float o[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int m = 4 * lq + v, i = m % 8;
+            const bool isq = m >= 8;
+            const bool ok = i < T && n < nrec && (n < f || (isq ? n - f <= i : n - f < i));
+            const float w = ok ? expf(sGc[wave][i] - Gkey) : 0.0f;
+            o[v] = (isq ? w : -w) * c1[v];
+        }
+        *reinterpret_cast<float4 *>(&cW[n][4 * lq]) = make_float4(o[0], o[1], o[2], o[3]);
+    };
+#pragma unroll
+    for (int x = 0; x < NTW; ++x) {
+        const int tile = wave + NW * x;
+        if (tile < ntile)
+            key_tile(tile, kt[x], Gn[x]);
+    }
+    for (int tile = wave + NW * NTW; TAIL && tile < ntile; tile += NW) {   // keys beyond the register window
+        const int n = 16 * tile + lm;
+        const bf16_t *kp = n < f ? kb + (size_t)n * D
+                                 : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
+        uint4 kk[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+            kk[st] = *reinterpret_cast<const uint4 *>(kp + 8 * lq + 32 * st);
+        key_tile(tile, kk, Gbuf[n < f ? n : 0]);
+    }
+    __syncthreads();
+
+    // ---- 4. stage 2: records, then state rows, on the fp32 matrix cores ------
+    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const int nquad = (f + 3) / 4;
+#pragma unroll
+    for (int sq = 0; sq < WQ; ++sq) {
+        if (sq < nquad) {   // uniform
+            const bool ok = 4 * sq + lq < f;
+            const float aw = cW[4 * sq + lq][lm];
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uq[sq].x : 0.0f, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uq[sq].y : 0.0f, acc1, 0, 0, 0);
+        }
+    }
+    for (int sq = WQ; TAIL && sq < nquad; ++sq) {
+        const int l = 4 * sq + lq;
+        const float2 u = *reinterpret_cast<const float2 *>(ub + (size_t)(l < f ? l : 0) * D + col2);
+        const float aw = cW[l][lm];
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.x : 0.0f, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.y : 0.0f, acc1, 0, 0, 0);
+    }
+    if constexpr (HAS_STATE) {
+#pragma unroll
+        for (int st = 0; st < D / 4; ++st) {
+            const float aw = sW[4 * st + lq][lm];
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].y, acc1, 0, 0, 0);
+        }
+    }
+    // acc*[v] = row m = 4 lq + v, column col2 (+1)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        *reinterpret_cast<float2 *>(&fin[4 * lq + v][col2]) = make_float2(acc0[v], acc1[v]);
+    __syncthreads();
+
+    // ---- 5. the T new rows among themselves; results ---------------------------
+    if (lane < 32) {
+        float uprev[TMX];
+#pragma unroll
+        for (int i = 0; i < TMX; ++i) {
+            if (i < T) {
+                float acc = to_f32(v_raw[i]) + fin[i][colf];
+                float ao = fin[8 + i][colf];
+#pragma unroll
+                for (int j = 0; j < TMX; ++j) {
+                    if (j < i) {
+                        acc = fmaf(cW[f + j][i], uprev[j], acc);     // K rows are stored negated
+                        ao = fmaf(cW[f + j][8 + i], uprev[j], ao);
+                    }
+                }
+                const float ui = bet[i] * acc;
+                ao = fmaf(cW[f + i][8 + i], ui, ao);
+                uprev[i] = ui;
+                a.out[(((size_t)b * T + i) * a.Hv + h) * D + colf] = a.scale * ao;
+                a.st.buf_u[(unit * cap + f + i) * D + colf] = ui;
+            }
+        }
+    }
+    if (tid < T)
+        a.st.buf_G[unit * cap + f + tid] = Gmine;   // tid < 8: lane % 8 == tid
+    if (h % r == 0 && wave == 0 && lm < T) {   // lanes holding k rows store them
+        bf16_t *kw = static_cast<bf16_t *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f + lm) * D + 8 * lq;
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+            *reinterpret_cast<uint4 *>(kw + 32 * st) = wa[st];
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 thread_local hipError_t g_last_hip_error = hipSuccess;
@@ -1204,9 +1467,31 @@ void launch_step_w(const StepArgs &a, int blocks, hipStream_t stream)
         launch_step_s<D, TIn, TM, 64>(a, blocks, stream);
 }
 
+template <int WREC>
+void launch_verify_mfma(const StepArgs &a, int blocks, hipStream_t stream)
+{
+    if (!a.st.state)
+        launch(kvb_verify_mfma_kernel<WREC, false, false>, blocks, stream, a);
+    else if (a.stream_state)
+        launch(kvb_verify_mfma_kernel<WREC, true, true>, blocks, stream, a);
+    else
+        launch(kvb_verify_mfma_kernel<WREC, true, false>, blocks, stream, a);
+}
+
 template <int D, typename TIn>
 void launch_step(const StepArgs &a, int blocks, hipStream_t stream)
 {
+    if constexpr (D == 128 && sizeof(TIn) == 2) {
+        if (a.T > 1) {   // several drafts: the matrix-core kernel; a request that fits has fill <= cap - T
+            if (a.cap - a.T <= 16)
+                launch_verify_mfma<16>(a, blocks, stream);
+            else if (a.cap - a.T <= 32)
+                launch_verify_mfma<32>(a, blocks, stream);
+            else
+                launch_verify_mfma<64>(a, blocks, stream);
+            return;
+        }
+    }
     if (a.T == 1)
         launch_step_w<D, TIn, 1>(a, blocks, stream);
     else if (a.T <= 4)
