@@ -40,18 +40,22 @@ def parse():
 
 
 class DecodeJob:
-    """Device-resident workload: store, a ring of token inputs, pre-marshalled calls."""
+    """Device-resident workload: one store holding every layer's slots, a ring of token
+    inputs, pre-marshalled calls (one per layer and ring entry)."""
 
     def __init__(self, w, ring=32, fused=True):
         import numpy as np
         import torch
         from paper_2605_19049_amd import kvb, synth
-        self.w, self.torch, self.kvb = w, torch, kvb
+        self.w, self.torch, self.kvb, self.np = w, torch, kvb, np
         dt = kvb.BF16 if w.in_dtype == "bf16" else kvb.F32
-        self.ds = kvb.DeviceStore(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt)
+        self.L = w.layers
+        self.ds = kvb.DeviceStore(w.B * self.L, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt)
         self.sh = kvb.shape(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt, 1.0)
-        self.st = self.ds.c()
-        self.slot = torch.arange(w.B, dtype=torch.int32, device="cuda")
+        # many layers: each state is next read a whole model pass later -> stream it
+        self.st = self.ds.c(flags=kvb.STORE_STREAM if self.L > 1 else 0)
+        self.slots = [torch.arange(l * w.B, (l + 1) * w.B, dtype=torch.int32, device="cuda")
+                      for l in range(self.L)]
         rng = np.random.default_rng(w.seed)
         tok = synth.token_stream(rng, w.B, ring, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype)
         tdt = torch.bfloat16 if w.in_dtype == "bf16" else torch.float32
@@ -66,41 +70,60 @@ class DecodeJob:
                 "g": torch.from_numpy(tok["g"][:, t].copy()).cuda(),
                 "beta": torch.from_numpy(tok["beta"][:, t].copy()).cuda()})
         self.out = torch.empty((w.B, w.Hv, w.dv), dtype=torch.float32, device="cuda")
+        # host mirror of every request's buffer fill (it evolves deterministically)
+        self.fills = np.zeros((self.L, w.B), np.int64)
+        if w.ragged:
+            # independent phases: all-zero records (k = u = 0, G = 0) are a valid buffer
+            self.fills = np.stack([synth.buffer_fills(rng, w.B, 0, w.C - 1) for _ in range(self.L)]).astype(np.int64)
+            self.ds.fill.copy_(torch.from_numpy(self.fills.reshape(-1).astype(np.int32)))
         self.t = 0          # tokens decoded so far (selects the ring entry)
         self.fused = fused
         self._bound = {}
 
     def _calls(self, stream):
-        key = stream
-        if key not in self._bound:
-            kvb = self.kvb
-            if self.fused:
-                dec = [kvb.bind("kvb_decode_flush", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
-                                x["beta"], self.out, self.w.C, stream) for x in self.tok]
-                fl = None
-            else:
-                dec = [kvb.bind("kvb_decode", self.sh, self.st, self.slot, x["q"], x["k"], x["v"], x["g"],
-                                x["beta"], self.out, stream) for x in self.tok]
-                fl = kvb.bind("kvb_flush", self.sh, self.st, self.slot, None, self.w.C, stream)
-            self._bound[key] = (dec, fl)
-        return self._bound[key]
+        if stream not in self._bound:
+            kvb, w = self.kvb, self.w
+            dec, fl = [], []
+            for l in range(self.L):
+                if self.fused:
+                    dec.append([kvb.bind("kvb_decode_flush", self.sh, self.st, self.slots[l], x["q"], x["k"], x["v"],
+                                         x["g"], x["beta"], self.out, w.C, stream) for x in self.tok])
+                    fl.append(None)
+                else:
+                    dec.append([kvb.bind("kvb_decode", self.sh, self.st, self.slots[l], x["q"], x["k"], x["v"],
+                                         x["g"], x["beta"], self.out, stream) for x in self.tok])
+                    fl.append(kvb.bind("kvb_flush", self.sh, self.st, self.slots[l], None, w.C, stream))
+            self._bound[stream] = (dec, fl)
+        return self._bound[stream]
+
+    def launch_bytes(self, fills):
+        """Algorithmic bytes of one decode(-flush) launch whose requests sit at `fills`."""
+        from paper_2605_19049_amd import traffic
+        lay, w = traffic.KVB, self.w
+        rd = lay.state + lay.token_in + fills * lay.record
+        wr = lay.token_out + (lay.state if self.fused else 0) * (fills + 1 >= w.C)
+        return float((rd + wr).sum()) * w.Hv
 
     def run(self, n, timers=None):
-        """n steps on the current stream; with `timers` (a list to fill), every decode launch
-        carries a kvb timer, which records that kernel's own begin/end timestamps."""
+        """n steps (each through every layer) on the current stream; with `timers` (a list to
+        fill), every decode launch carries a kvb timer, which records that kernel's own
+        begin/end timestamps; the entry also notes the launch's algorithmic bytes."""
         torch = self.torch
         dec, fl = self._calls(torch.cuda.current_stream().cuda_stream)
         for _ in range(n):
-            d = dec[self.t % self.ring]
-            if timers is not None:
-                tm = self.kvb.Timer()
-                tm.arm()
-                d()
-                timers.append((tm, self.t % self.w.C))
-            else:
-                d()
-            if fl is not None:
-                fl()
+            r = self.t % self.ring
+            for l in range(self.L):
+                if timers is not None:
+                    tm = self.kvb.Timer()
+                    tm.arm()
+                    dec[l][r]()
+                    timers.append((tm, self.launch_bytes(self.fills[l]),
+                                   bool((self.fills[l] + 1 >= self.w.C).any())))
+                else:
+                    dec[l][r]()
+                if fl[l] is not None:
+                    fl[l]()
+            self.fills = (self.fills + 1) % self.w.C
             self.t += 1
 
 
@@ -229,23 +252,25 @@ def main():
         del src, dst
     fused = args.step == "fused"
     job = DecodeJob(w, fused=fused)
+    L = job.L
     # untimed: build a real committed state by decoding a prompt-sized prefix, then W warm-up steps
     job.run(w.prefix + W)
     torch.cuda.synchronize()
-    t_start = job.t
+    t_start, fills_start = job.t, job.fills.copy()
     bufs = (job.ds.state, job.ds.buf_k, job.ds.buf_u, job.ds.buf_G, job.ds.fill)
 
     graph = None
     if args.mode == "graph":
-        snap = [x.clone() for x in bufs]
+        snap = [x.clone() for x in bufs[1:]] if L > 1 else [x.clone() for x in bufs]
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             job.run(K)
         torch.cuda.synchronize()
         # make sure the store is exactly where the captured work expects it
-        for dst, src in zip(bufs, snap):
+        for dst, src in zip(bufs[1:] if L > 1 else bufs, snap):
             dst.copy_(src)
-        job.t = t_start
+        del snap
+        job.t, job.fills = t_start, fills_start.copy()
         torch.cuda.synchronize()
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -254,63 +279,67 @@ def main():
     e0.record()
     if graph is not None:
         graph.replay()
-        job.t = t_start + K
+        job.t, job.fills = t_start + K, (fills_start + K) % w.C
     else:
         job.run(K)
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     sec = e0.elapsed_time(e1) * 1e-3
+    n_launch = K * L
     assert int(job.ds.status.sum().item()) == 0, "a buffer overflowed during the bench"
 
-    # The same K steps again, eager, every decode launch carrying a kernel timer (begin/end
+    # The same steps again, eager, every decode launch carrying a kernel timer (begin/end
     # timestamps of that kernel alone): the dominant kernel's duration, with its algorithmic
-    # bytes at the fill it actually ran at.
+    # bytes at the fills it actually ran at.
     timers = []
-    job.run(K, timers)
+    job.run(min(K, max(1, 1024 // L)), timers)
     torch.cuda.synchronize()
     units = w.B * w.Hv
-    dec_us = [tm.us() for tm, _ in timers]
+    dec_us = [tm.us() for tm, _, _ in timers]
+    dec_bytes = [by for _, by, _ in timers]
+    for tm, _, _ in timers:
+        tm.close()
+    lay = traffic.KVB
     if fused:
-        dec_bytes = [traffic.total(traffic.decode_flush_rw(traffic.KVB, f, w.C)) * units for _, f in timers]
-        cycle_bytes = traffic.total(traffic.fused_cycle_rw(traffic.KVB, w.C)) * units
-        kname = "kvb_step_kernel<128,bf16,TM=1,W=16,state,fused> (kvb_decode_flush)"
+        cycle_bytes = traffic.total(traffic.fused_cycle_rw(lay, w.C)) * units
+        kname = "kvb_step_kernel<128,bf16,TM=1,W=%d,state,fused> (kvb_decode_flush)" % (16 if w.cap <= 16 else 32 if w.cap <= 32 else 64)
         step_desc = "kvb_decode_flush(threshold=C)"
     else:
-        dec_bytes = [traffic.total(traffic.decode_rw(traffic.KVB, f)) * units for _, f in timers]
-        cycle_bytes = traffic.total(traffic.chunk_cycle_rw(traffic.KVB, w.C)) * units
-        kname = "kvb_step_kernel<128,bf16,TM=1,W=16,state> (kvb_decode)"
+        cycle_bytes = traffic.total(traffic.chunk_cycle_rw(lay, w.C)) * units
+        kname = "kvb_step_kernel<128,bf16,TM=1,W=%d,state> (kvb_decode)" % (16 if w.cap <= 16 else 32 if w.cap <= 32 else 64)
         step_desc = "kvb_decode + kvb_flush(threshold=C)"
-    for tm, _ in timers:
-        tm.close()
     dec_avg_us = sum(dec_us) / len(dec_us)
     achieved = sum(dec_bytes) / (sum(dec_us) * 1e-6) / 1e9
-    noflush = [(u, b) for u, b, (_, f) in zip(dec_us, dec_bytes, timers) if f + 1 < w.C]
+    noflush = [(u, by) for u, by, (_, _, fl_) in zip(dec_us, dec_bytes, timers) if not fl_]
+    per_layer_step = sec / n_launch
 
     res = {
-        "metric": "gdn_decode_tokens_per_s_per_layer", "value": w.B * K / sec, "unit": "tokens/s/layer",
+        "metric": "gdn_decode_tokens_per_s_per_layer", "value": w.B / per_layer_step, "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": sec / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hk": w.Hk, "Hv": w.Hv, "dk": w.dk, "dv": w.dv,
-                   "C": w.C, "cap": w.cap, "in_dtype": w.in_dtype, "state_dtype": "f32",
-                   "step": step_desc, "launch": args.mode,
-                   "state_MiB": units * w.dk * w.dv * 4 / 2 ** 20},
-        "full_cycle": {"algorithmic_bytes_per_step": cycle_bytes,
-                       "algorithmic_GBps": cycle_bytes / (sec / K) / 1e9,
-                       "frac_of_hbm_peak": cycle_bytes / (sec / K) / 1e9 / HBM_PEAK_GBS,
+                   "C": w.C, "cap": w.cap, "layers": L, "in_dtype": w.in_dtype, "state_dtype": "f32",
+                   "step": step_desc + (" through each of %d layers" % L if L > 1 else ""), "launch": args.mode,
+                   "state_MiB": L * units * w.dk * w.dv * 4 / 2 ** 20},
+        "full_cycle": {"algorithmic_bytes_per_layer_step": cycle_bytes,
+                       "algorithmic_GBps": cycle_bytes / per_layer_step / 1e9,
+                       "frac_of_hbm_peak": cycle_bytes / per_layer_step / 1e9 / HBM_PEAK_GBS,
+                       "us_per_layer_step": per_layer_step * 1e6,
                        "host_wall_ms_per_step": wall / K * 1e3},
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, fused),
                      "avg_launch_us": dec_avg_us, "launches": len(dec_us),
                      "algorithmic_bytes_per_launch_avg": sum(dec_bytes) / len(dec_bytes),
-                     "steps_without_state_update": {
-                         "avg_launch_us": sum(u for u, _ in noflush) / len(noflush),
-                         "achieved": sum(b for _, b in noflush) / (sum(u for u, _ in noflush) * 1e-6) / 1e9},
                      "timing": "begin/end timestamps of each launch of this kernel (kvb timer = "
-                               "hipExtLaunchKernel events), eager re-run of the same K steps"},
+                               "hipExtLaunchKernel events), eager re-run of the same steps"},
     }
+    if noflush:
+        res["roofline"]["launches_without_state_update"] = {
+            "avg_launch_us": sum(u for u, _ in noflush) / len(noflush),
+            "achieved": sum(by for _, by in noflush) / (sum(u for u, _ in noflush) * 1e-6) / 1e9}
     if not args.no_other_paths:
         res["other_paths"] = time_other_paths(torch, kvb, synth, traffic)
     if not args.no_cpu_baseline:

@@ -68,6 +68,7 @@ class Workload:
     layers: int = 1
     seed: int = 0
     prefix: int = 64  # tokens folded into the initial state
+    ragged: bool = False  # requests start at independent buffer fills ~U{0..C-1}
 
 
 # The five workloads the build is measured / parity-checked on.
@@ -81,7 +82,7 @@ WORKLOADS = {
     "short_direct": Workload("short_direct", B=256, Hk=16, Hv=32, dk=128, dv=128, C=64,
                              cap=64, in_dtype="bf16", Lmax=64, seed=4, prefix=0),
     "long_mixed": Workload("long_mixed", B=512, Hk=16, Hv=32, dk=128, dv=128, C=64,
-                           cap=64, in_dtype="bf16", steps=128, layers=36, seed=5),
+                           cap=64, in_dtype="bf16", steps=128, layers=36, seed=5, ragged=True),
 }
 
 
