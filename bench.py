@@ -32,6 +32,8 @@ def parse():
                     help="graph: the K timed steps are one HIP graph launch; eager: one launch per kernel")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the workload's batch size (e.g. 512: 1 GiB of state, beyond the last-level cache)")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="override the chunk size C (and cap); 1 = the fused recurrent step, for the Fig. 3 style sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -240,6 +242,9 @@ def main():
     if args.batch:
         import dataclasses
         w = dataclasses.replace(w, B=args.batch, name="%s(B=%d)" % (w.name, args.batch))
+    if args.chunk:
+        import dataclasses
+        w = dataclasses.replace(w, C=args.chunk, cap=args.chunk, name="%s(C=%d)" % (w.name, args.chunk))
     K, W = args.steps, args.warmup
 
     if args.copy_calibration:

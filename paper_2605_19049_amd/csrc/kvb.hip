@@ -880,76 +880,94 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// kvb_direct for bf16 inputs and d = 128: the two Gram matrices K K^T and Q K^T are dense
-// contractions over dk = 128 of operands that are bf16 to begin with, so they go on the
-// matrix cores (v_mfma_f32_16x16x32_bf16, exact products, fp32 accumulate).  The unit
-// lower-triangular solve for U and the product (Q K^T . Gamma) U have fp32 operands and a
-// sequential dependence over rows; they run on the vector ALUs, two lanes per dv column.
+// kvb_direct for bf16 inputs and d = 128, on the matrix cores throughout.
 //
-// MFMA operand layout used below (16x16x32): lane l supplies row l%16 of A (resp. column
-// l%16 of B) at k = 8*(l/16) .. +7; it receives C[4*(l/16) + v][l%16], v = 0..3.
+// The context is cut into blocks of 16 rows.  With N_il = beta_i Gamma_il (k_i.k_l) (l < i)
+// and M_il = Gamma_il (q_i.k_l) (l <= i) the parallel form (Eq. 13) is
+//     (I + N) U = Diag(beta) V,      O = M U,
+// solved block row by block row:  U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),
+// T_d = (I + N_dd)^-1 = (I - N)(I + N^2)(I + N^4)(I + N^8)   (N_dd is strictly lower, N^16 = 0),
+// O_d = sum_{e<=d} M_de U_e.
+//   * Gram tiles (k.k, q.k over dk = 128, bf16 operands): v_mfma_f32_16x16x32_bf16.
+//   * everything after that has fp32 operands: v_mfma_f32_16x16x4_f32 (exact products).
+//
+// Register chaining.  Call "A-form" of a 16x16 matrix X the register layout in which lane l
+// holds X[l%16][4*(l/16)+v], v = 0..3, and "B-form" the one with X[4*(l/16)+v][l%16].  An
+// MFMA result is in B-form; feeding four k-steps with (a = xa[v], b = yb[v]) gives the
+// B-form of X Y, and swapping the operands, (a = yb[v], b = xa[v]), gives the A-form of X Y.
+// A Gram tile computed as (rows of block e) x (rows of block d) lands directly in A-form of
+// the (d, e) tile, so no value ever needs to move between lanes: tiles shared between waves
+// go through LDS as whole per-lane float4s.  Each wave owns 32 dv columns (two column tiles).
 // ---------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-// Row I of the solve, for the lane pair that owns dv column j (fully unrolled over I so
-// that the delta values stay in registers).  Lane parity p owns rows l with (l / 4) % 2 == p,
-// kept in ureg[4 * (l / 8) + l % 4]; a row's register holds v_l until u_l replaces it.
-template <int I, int LM, int D>
-__device__ __forceinline__ void direct_row(const float (&cK)[LM][LM], const float (&cQ)[LM][LM],
-                                           const float (&sB)[LM], const float (&sD)[LM], float (&ureg)[LM / 2],
-                                           int p, float scale, float *out_row, float *u_row)
+// B-form of X Y from X in A-form and Y in B-form (swap the arguments for the A-form of X Y).
+__device__ __forceinline__ f32x4_t mm16(const f32x4_t &xa, const f32x4_t &yb, f32x4_t acc)
 {
-    constexpr int NB = (I + 7) / 8;   // blocks of 8 earlier rows that touch rows < I
-    float acck = 0.0f, accq = 0.0f;
 #pragma unroll
-    for (int m = 0; m < NB; ++m) {
-        // coefficients of rows >= I are zero, so a partly covered block needs no masking
-        const float4 ck = *reinterpret_cast<const float4 *>(&cK[I][8 * m + 4 * p]);
-        const float4 cq = *reinterpret_cast<const float4 *>(&cQ[I][8 * m + 4 * p]);
-        acck = fmaf(ck.x, ureg[4 * m + 0], acck); accq = fmaf(cq.x, ureg[4 * m + 0], accq);
-        acck = fmaf(ck.y, ureg[4 * m + 1], acck); accq = fmaf(cq.y, ureg[4 * m + 1], accq);
-        acck = fmaf(ck.z, ureg[4 * m + 2], acck); accq = fmaf(cq.z, ureg[4 * m + 2], accq);
-        acck = fmaf(ck.w, ureg[4 * m + 3], acck); accq = fmaf(cq.w, ureg[4 * m + 3], accq);
-    }
-    acck += __shfl_xor(acck, 1);
-    accq += __shfl_xor(accq, 1);
-    constexpr int R = 4 * (I / 8) + I % 4;      // register of row I in its owner lane
-    const float ui = sB[I] * (ureg[R] - acck);
-    const float o = fmaf(sD[I], ui, accq);
-    if (p == (I / 4) % 2) {
-        ureg[R] = ui;
-        *out_row = scale * o;
-        *u_row = ui;
-    }
+    for (int v = 0; v < 4; ++v)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[v], yb[v], acc, 0, 0, 0);
+    return acc;
 }
 
-template <int I0, int LM, int D>
-__device__ __forceinline__ void direct_rows8(const float (&cK)[LM][LM], const float (&cQ)[LM][LM],
-                                             const float (&sB)[LM], const float (&sD)[LM], float (&ureg)[LM / 2],
-                                             int p, float scale, int L, float *out0, size_t out_stride, float *u0)
+// exp for arguments that are differences of cumulative log decays (<= 0, a few tens at
+// most): one multiply and the hardware exp2; relative error about |x| * 2^-23, far inside
+// the 2e-3 bound of the bf16 paths that use it.
+__device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
+
+template <typename... Ts>
+constexpr uint32_t pack2(Ts... xs)
 {
-    // rows I0 .. I0+7; L is uniform over the workgroup
-#define KVB_ROW(X)                                                                                          \
-    if (I0 + X < L)                                                                                         \
-        direct_row<I0 + X, LM, D>(cK, cQ, sB, sD, ureg, p, scale, out0 + (size_t)(I0 + X) * out_stride,      \
-                                  u0 + (size_t)(I0 + X) * D);
-    KVB_ROW(0) KVB_ROW(1) KVB_ROW(2) KVB_ROW(3) KVB_ROW(4) KVB_ROW(5) KVB_ROW(6) KVB_ROW(7)
-#undef KVB_ROW
+    uint32_t r = 0;
+    int sh = 0;
+    ((r |= (uint32_t)xs << sh, sh += 2), ...);
+    return r;
 }
 
-__global__ __launch_bounds__(NT) void kvb_direct_mfma_kernel(const DirectArgs a)
+// Raw Gram tile from rows staged in LDS (row stride GS bf16 elements): lane l reads row l%16
+// of the A-side block and of the B-side block at k = 8*(l/16) + 32*step.  acc[v] =
+// (A-side row 4*(l/16)+v) . (B-side row l%16), i.e. the A-form of the (B-block, A-block) tile.
+template <int GS>
+__device__ __forceinline__ f32x4_t gram16(const bf16_t *arow, const bf16_t *brow, int lq)
+{
+    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
+        const uint4 bv = *reinterpret_cast<const uint4 *>(brow + 8 * lq + 32 * st);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                    __builtin_bit_cast(bf16x8_t, bv), c, 0, 0, 0);
+    }
+    return c;
+}
+
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void kvb_direct_mfma_kernel(
+    const DirectArgs a)
 {
     constexpr int D = 128;
     constexpr int LM = KVB_MAX_DIRECT_LEN;
-    static_assert(LM == 64, "tile table below is for 4 x 4 tiles of 16");
-    __shared__ __attribute__((aligned(16))) float cK[LM][LM];  // Gamma_il (k_i.k_l) for l < i, else 0
-    __shared__ __attribute__((aligned(16))) float cQ[LM][LM];  // Gamma_il (q_i.k_l) for l < i, else 0
+    constexpr int NB = LM / 16;                 // blocks of 16 rows (4)
+    constexpr int NLOW = NB * (NB + 1) / 2;     // lower-triangular block pairs (10)
+    constexpr int GS = D + 8;                   // LDS row stride of the staged keys / queries (272 B:
+                                                // consecutive rows start 4 banks apart)
+    static_assert(NB == NW, "one diagonal block per wave");
+    // One LDS region, used twice: first the staged K and Q rows (bf16), then, once every
+    // raw Gram tile sits in registers, the weighted tiles in A-form (one float4 per lane):
+    // -N_de (d > e), M_de (d >= e), T_d.
+    constexpr int STAGE_BYTES = 2 * LM * GS * 2;
+    constexpr int TILE_BYTES = (2 * NLOW + NB) * 64 * 16;
+    __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
     __shared__ float sG[LM];
     __shared__ float sB[LM];
-    __shared__ float sD[LM];                                   // q_i.k_i (the l = i term of the output)
+    bf16_t *sK = reinterpret_cast<bf16_t *>(region);
+    bf16_t *sQ = sK + LM * GS;
+    float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
+    float4(*tM)[64] = tN + NLOW;
+    float4(*tT)[64] = tM + NLOW;
 
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int c16 = lane % 16, lq = lane / 16;
     const int lb = logical_block();
     const int b = lb / a.Hv;
     const int h = lb % a.Hv;
@@ -975,19 +993,45 @@ __global__ __launch_bounds__(NT) void kvb_direct_mfma_kernel(const DirectArgs a)
     const bf16_t *qin = static_cast<const bf16_t *>(a.q);
     const bf16_t *kin = static_cast<const bf16_t *>(a.k);
     const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const int nb = (L + 15) / 16;
+    auto tri = [](int d, int e) { return d * (d + 1) / 2 + e; };
 
-    // this lane's v values (rows past the context are clamped to a valid row and never used)
-    const int j = tid / 2, p = tid % 2;
-    bf16_t v_raw[LM / 2];
+    // ---- all global loads of the workgroup, issued together ---------------------
+    // K and Q rows, 16 bytes per thread and pass (pass p = rows 16 p .. 16 p + 15)
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    u32x4_t kst[NB], qst[NB];
+    const int srow = tid / 16, sc8 = tid % 16;
+    // (uniform 64-bit base + 32-bit per-lane offset keeps the address arithmetic out of the VGPRs)
+    const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
+    const uint32_t qk_stride = (uint32_t)a.Hk * D, v_stride = (uint32_t)a.Hv * D;
 #pragma unroll
-    for (int n = 0; n < LM / 2; ++n) {
-        const int l = min(8 * (n / 4) + 4 * p + n % 4, L - 1);
-        v_raw[n] = vin[(((size_t)b * Lmax + l) * a.Hv + h) * D + j];
+    for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
+        const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
+        kst[p] = u32x4_t{0u, 0u, 0u, 0u};
+        qst[p] = kst[p];
+        if (p < nb) {   // uniform
+            kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
+            qst[p] = *reinterpret_cast<const u32x4_t *>(qbase + o);
+        }
     }
-
+    // v in B-form: rows 16 d + 4 lq + v, this lane's two adjacent columns 32 wave + 2 c16, + 1
+    const int col2 = 32 * wave + 2 * c16;
+    uint32_t v_raw[NB][4];
+#pragma unroll
+    for (int d = 0; d < NB; ++d)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            v_raw[d][v] = 0u;
+            if (d < nb)   // uniform
+                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+        }
     // cumulative log decay (inclusive scan over the wave) and beta
     if (wave == 0) {
         float gv = lane < L ? a.g[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+        const float bv = lane < L ? a.beta[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const float t = __shfl_up(gv, off);
@@ -995,91 +1039,139 @@ __global__ __launch_bounds__(NT) void kvb_direct_mfma_kernel(const DirectArgs a)
                 gv += t;
         }
         sG[lane] = gv;
-        sB[lane] = lane < L ? a.beta[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+        sB[lane] = bv;
+        if (lane < L)
+            a.st.buf_G[unit * a.cap + lane] = gv;
     }
-
-    // ---- Gram tiles on the matrix cores --------------------------------------
-    const int ntile = (L + 15) / 16;
-    f32x4_t accK[3], accQ[3];
-    int tile_i[3], tile_j[3];
-    {
-        // lower-triangular 16x16 tiles of the 64x64 matrices, dealt to the 4 waves
-        constexpr int TI[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
-        constexpr int TJ[10] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+    // stage K, Q; the thread that loaded a piece of K also appends it to the buffer
+    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * a.cap * D;
 #pragma unroll
-        for (int n = 0; n < 3; ++n) {
-            const int t = wave + 4 * n;
-            tile_i[n] = t < 10 ? TI[t] : 99;
-            tile_j[n] = t < 10 ? TJ[t] : 0;
-            accK[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            accQ[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            if (tile_i[n] < ntile) {   // uniform over the wave
-                const int ri = min(16 * tile_i[n] + lane % 16, L - 1);
-                const int rj = min(16 * tile_j[n] + lane % 16, L - 1);
-                const size_t oi = (((size_t)b * Lmax + ri) * a.Hk + hk) * D + 8 * (lane / 16);
-                const size_t oj = (((size_t)b * Lmax + rj) * a.Hk + hk) * D + 8 * (lane / 16);
-                uint4 ak[D / 32], aq[D / 32], bk[D / 32];
-#pragma unroll
-                for (int st = 0; st < D / 32; ++st) {
-                    ak[st] = *reinterpret_cast<const uint4 *>(kin + oi + 32 * st);
-                    aq[st] = *reinterpret_cast<const uint4 *>(qin + oi + 32 * st);
-                    bk[st] = *reinterpret_cast<const uint4 *>(kin + oj + 32 * st);
-                }
-#pragma unroll
-                for (int st = 0; st < D / 32; ++st) {
-                    accK[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ak[st]),
-                                                                      __builtin_bit_cast(bf16x8_t, bk[st]), accK[n], 0, 0, 0);
-                    accQ[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq[st]),
-                                                                      __builtin_bit_cast(bf16x8_t, bk[st]), accQ[n], 0, 0, 0);
-                }
-            }
-        }
-    }
-    __syncthreads();   // sG visible
-#pragma unroll
-    for (int n = 0; n < 3; ++n) {
-        if (tile_i[n] < ntile) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int i = 16 * tile_i[n] + 4 * (lane / 16) + v;
-                const int jj = 16 * tile_j[n] + lane % 16;
-                const float w = (i < L && jj < i) ? expf(sG[i] - sG[jj]) : 0.0f;
-                cK[i][jj] = w * accK[n][v];
-                cQ[i][jj] = w * accQ[n][v];
-                if (i == jj)
-                    sD[i] = accQ[n][v];
-            }
+    for (int p = 0; p < NB; ++p) {
+        if (p < nb) {   // uniform
+            *reinterpret_cast<u32x4_t *>(sK + (16 * p + srow) * GS + 8 * sc8) = kst[p];
+            *reinterpret_cast<u32x4_t *>(sQ + (16 * p + srow) * GS + 8 * sc8) = qst[p];
+            if (h % r == 0 && 16 * p + srow < L)
+                *reinterpret_cast<u32x4_t *>(kb + (size_t)(16 * p + srow) * D + 8 * sc8) = kst[p];
         }
     }
     __syncthreads();
 
-    // ---- the solve and the outputs, row after row, delta values in registers ----
-    {
-        float ureg[LM / 2];
+    // ---- raw Gram tiles: this wave's diagonal k.k tile and its share of the others ----
+    // off-diagonal k.k pairs (d > e): 6; q.k pairs (d >= e): 10; dealt round-robin
+    // (two bits per entry, packed: a table indexed by the wave number would live in scratch)
+    constexpr uint32_t PDB = pack2(1, 2, 2, 3, 3, 3, 0, 1, 1, 2, 2, 2, 3, 3, 3, 3);
+    constexpr uint32_t PEB = pack2(0, 0, 1, 0, 1, 2, 0, 0, 1, 0, 1, 2, 0, 1, 2, 3);
+    auto PD = [](int t) { return (int)((PDB >> (2 * t)) & 3u); };
+    auto PE = [](int t) { return (int)((PEB >> (2 * t)) & 3u); };
+    f32x4_t gdiag = {0.f, 0.f, 0.f, 0.f};
+    if (wave < nb)
+        gdiag = gram16<GS>(sK + (16 * wave + c16) * GS, sK + (16 * wave + c16) * GS, lq);
+    f32x4_t gsh[4];
 #pragma unroll
-        for (int n = 0; n < LM / 2; ++n)
-            ureg[n] = to_f32(v_raw[n]);
-        float *out0 = a.out + (((size_t)b * Lmax) * a.Hv + h) * D + j;
-        const size_t ostride = (size_t)a.Hv * D;
-        float *u0 = a.st.buf_u + unit * a.cap * D + j;
-        direct_rows8<0, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 8) direct_rows8<8, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 16) direct_rows8<16, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 24) direct_rows8<24, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 32) direct_rows8<32, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 40) direct_rows8<40, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 48) direct_rows8<48, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
-        if (L > 56) direct_rows8<56, LM, D>(cK, cQ, sB, sD, ureg, p, a.scale, L, out0, ostride, u0);
+    for (int n = 0; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t), e = PE(t);
+        gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (d < nb)   // uniform
+            gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, (t < 6 ? sK : sQ) + (16 * d + c16) * GS, lq);
     }
+    __syncthreads();   // every wave is done with the staged rows: the region now takes the tiles
 
-    if (tid < L)
-        a.st.buf_G[unit * a.cap + tid] = sG[tid];
-    if (h % r == 0) {
-        bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * a.cap * D;
-        for (int c = tid; c < L * (D / 8); c += NT) {
-            const int i = c / (D / 8), e8 = c % (D / 8);
-            *reinterpret_cast<uint4 *>(kb + (size_t)i * D + 8 * e8) =
-                *reinterpret_cast<const uint4 *>(kin + (((size_t)b * Lmax + i) * a.Hk + hk) * D + 8 * e8);
+    // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t), e = PE(t);
+        if (d < nb) {
+            const int i = 16 * d + c16;
+            const bool isq = t >= 6;
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int l = 16 * e + 4 * lq + v;
+                const bool ok = i < L && (isq ? l <= i : l < i);
+                const float w = ok ? fast_exp(sG[i] - sG[l]) : 0.0f;
+                o[v] = (isq ? w : -sB[i] * w) * gsh[n][v];
+            }
+            const float4 o4 = make_float4(o[0], o[1], o[2], o[3]);
+            if (isq)
+                tM[tri(d, e)][lane] = o4;
+            else
+                tN[tri(d, e)][lane] = o4;
+        }
+    }
+    // T_d for d = wave.  The raw diagonal tile is symmetric, so the same registers give the
+    // A-form (row 16 d + c16, column 16 d + 4 lq + v) and the B-form (row and column swapped).
+    if (wave < nb) {
+        const int d = wave;
+        f32x4_t na, nbm, ia;   // N in both forms; identity mask (the same in both forms)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ia_i = 16 * d + c16, ia_l = 16 * d + 4 * lq + v;    // A-form indices
+            const int ib_i = ia_l, ib_l = ia_i;                            // B-form indices
+            const float wa = (ia_i < L && ia_l < ia_i) ? sB[ia_i] * fast_exp(sG[ia_i] - sG[ia_l]) : 0.0f;
+            const float wb = (ib_i < L && ib_l < ib_i) ? sB[ib_i] * fast_exp(sG[ib_i] - sG[ib_l]) : 0.0f;
+            na[v] = wa * gdiag[v];
+            nbm[v] = wb * gdiag[v];
+            ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
+        }
+        const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+        const f32x4_t n2b = mm16(na, nbm, z), n2a = mm16(nbm, na, z);
+        const f32x4_t n4b = mm16(n2a, n2b, z), n4a = mm16(n2b, n2a, z);
+        const f32x4_t n8b = mm16(n4a, n4b, z);
+        // A-form of (I - N)(I + N^2), then x (I + N^4), then x (I + N^8)
+        f32x4_t p = mm16(ia + n2b, ia - na, z);
+        p = mm16(ia + n4b, p, z);
+        p = mm16(ia + n8b, p, z);
+        tT[d][lane] = make_float4(p[0], p[1], p[2], p[3]);
+    }
+    __syncthreads();
+
+    // ---- block forward substitution and outputs, this wave's 32 columns ----------
+    // column tile c of the wave holds columns 32 wave + 2 n + c (n = 0..15): a lane's two
+    // tiles are adjacent columns, so v arrives as one 4-byte load and results leave as float2
+    f32x4_t U[NB][2];
+    float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
+    float *up = a.st.buf_u + unit * a.cap * D;
+#pragma unroll
+    for (int d = 0; d < NB; ++d) {
+        if (d < nb) {   // uniform
+            f32x4_t acc[2], o[2];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                const float bi = i < L ? sB[i] : 0.0f;
+                acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
+                acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
+            }
+            o[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            o[1] = o[0];
+#pragma unroll
+            for (int e = 0; e < d; ++e) {
+                const float4 n4 = tN[tri(d, e)][lane];
+                const float4 m4 = tM[tri(d, e)][lane];
+                const f32x4_t nn = {n4.x, n4.y, n4.z, n4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    acc[c] = mm16(nn, U[e][c], acc[c]);
+                    o[c] = mm16(mm, U[e][c], o[c]);
+                }
+            }
+            const float4 t4 = tT[d][lane];
+            const float4 m4 = tM[tri(d, d)][lane];
+            const f32x4_t tt = {t4.x, t4.y, t4.z, t4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                U[d][c] = mm16(tt, acc[c], f32x4_t{0.f, 0.f, 0.f, 0.f});
+                o[c] = mm16(mm, U[d][c], o[c]);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                if (i < L) {
+                    *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
+                        make_float2(a.scale * o[0][v], a.scale * o[1][v]);
+                    *reinterpret_cast<float2 *>(up + ((uint32_t)i * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                }
+            }
         }
     }
     if (h == 0 && tid == 0)
