@@ -536,3 +536,58 @@ def test_long_mixed_full_size_sampled():
     say("long_mixed full size: rel err out/state on %d sampled pairs: %.2e %.2e" % (P, e[0], e[1]))
     assert max(e) < H.TOL["bf16"]
     assert bool(torch.isfinite(ds.state).all())
+
+
+@pytest.mark.parametrize("Hk, Hv", [(3, 3), (1, 4), (2, 8)])
+def test_head_grouping_ratios(Hk, Hv):
+    """One, four and (again) four v-heads per qk-head, through decode, flush, verify and direct."""
+    d, C, B = 128, 8, 3
+    rng = np.random.default_rng(80 + Hv)
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, "bf16", 8)
+    tok = synth.token_stream(rng, B, 19, Hk, Hv, d, d, "bf16")
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+    o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=True)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    assert max(H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref)) < H.TOL["bf16"]
+    e = _verify_case(B=B, Hk=Hk, Hv=Hv, d=d, C=C, cap=C + 3, T=4, in_dtype="bf16", seed=90 + Hv)
+    assert max(e) < H.TOL["bf16"]
+    e = _direct_case(B=B, Hk=Hk, Hv=Hv, d=d, Lmax=40, cap=48, in_dtype="bf16", seed=95 + Hv)
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_largest_buffer_and_most_drafts():
+    """cap = 128 (the paper's upper end, d records) with 8 drafts on nearly full buffers: the
+    record windows' tail paths of both the decode and the verify kernel."""
+    e = _verify_case(B=5, Hk=1, Hv=2, d=128, C=120, cap=128, T=8, in_dtype="bf16", seed=97, fill_hi=119)
+    say("cap=128 T=8 rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    e = _verify_case(B=3, Hk=1, Hv=2, d=128, C=40, cap=48, T=8, in_dtype="f32", seed=98, fill_hi=39)
+    say("cap=48 T=8 fp32 rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["f32"]
+
+
+def test_kv_only_verify_and_stream_hint_do_not_change_results():
+    """kvb_verify with no state (KV-only contexts, Sec. 3.4) and the non-temporal state loads
+    (a cache hint) against the same oracle / against the default path bit for bit."""
+    e = _verify_case(B=4, Hk=2, Hv=4, d=128, C=16, cap=20, T=4, in_dtype="bf16", seed=99, kv_only=True)
+    assert max(e) < H.TOL["bf16"]
+    rng = np.random.default_rng(101)
+    B, Hk, Hv, d, C = 3, 2, 4, 128, 8
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    tok = H.upload_tokens(synth.token_stream(rng, B, 11, Hk, Hv, d, d, "bf16"), "bf16")
+    res = []
+    for flags in (kvb.STORE_RESIDENT, kvb.STORE_STREAM):
+        lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+        lay.set_state(S0)
+        outs = torch.empty((11, B, Hv, d), dtype=torch.float32, device="cuda")
+        for t in range(11):
+            kvb.kvb_decode_flush(lay.shape(), lay.ds.c(flags=flags), lay.slot, *[H.step_view(tok, t)[n] for n in
+                                 ("q", "k", "v", "g", "beta")], outs[t], C)
+        vout = torch.empty((B, 3, Hv, d), dtype=torch.float32, device="cuda")
+        vt = {n: x[:, :3].contiguous() for n, x in tok.items()}
+        kvb.kvb_verify(lay.shape(), lay.ds.c(flags=flags), lay.slot, 3, vt["q"], vt["k"], vt["v"], vt["g"],
+                       vt["beta"], vout)
+        torch.cuda.synchronize()
+        res.append((outs.clone(), vout.clone(), lay.ds.state.clone(), lay.ds.buf_u.clone()))
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
