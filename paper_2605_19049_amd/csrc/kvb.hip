@@ -605,10 +605,63 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                 sreg[p].x *= gam; sreg[p].y *= gam; sreg[p].z *= gam; sreg[p].w *= gam;
             }
             const float *ub = a.st.buf_u + unit * cap * D;
-            for (int l0 = 0; l0 < m; l0 += LT) {
+            // one LDS tile of LT records: record f itself comes from this workgroup's registers
+            auto inject_new = [&](int l0) {
+                if (f >= l0 && f < l0 + LT) {
+                    if (grp == 0) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            kh[f - l0][8 * sub + e] = k8[e];
+                    }
+                    if (tid < D)
+                        uu[f - l0][tid] = u_new;
+                }
+            };
+            auto apply_tile = [&](int l0) {
+                const int nl = min(LT, m - l0);
+                for (int l = 0; l < nl; ++l) {
+                    const float4 u = *reinterpret_cast<const float4 *>(&uu[l][4 * c4]);
+#pragma unroll
+                    for (int p = 0; p < NPASS; ++p)
+                        fma4(sreg[p], kh[l][rg + RPP * p], u);
+                }
+            };
+            int l_done = 0;
+            if constexpr (NG == LT && 2 * RPP == LT && WREC <= 32) {
+                // d = 128: a window pass of keys is exactly one tile, two passes of delta values
+                // fill it, so the tiles inside the register window need no second trip to memory
+                // (not for the 64-record window: keeping it alive this long costs a workgroup per CU)
+#pragma unroll
+                for (int p = 0; p < KP; ++p) {
+                    if (LT * p < m) {   // uniform
+                        __syncthreads();
+                        const int l = LT * p + grp;
+                        float kx[8];
+                        unpack8(kl_raw[p], kx);
+                        const float w = l < f ? expf(Gc[0] - Gl[p]) : 0.0f;
+                        if (l != f) {   // row f of the tile belongs to inject_new
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                kh[grp][8 * sub + e] = l < f ? w * kx[e] : 0.0f;
+                        }
+#pragma unroll
+                        for (int jj = 0; jj < 2; ++jj) {
+                            const int lu = LT * p + RPP * jj + rg;
+                            const float4 u = ur[2 * p + jj];
+                            if (lu != f)
+                                *reinterpret_cast<float4 *>(&uu[RPP * jj + rg][4 * c4]) =
+                                    lu < f ? u : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+                        inject_new(LT * p);
+                        __syncthreads();
+                        apply_tile(LT * p);
+                    }
+                }
+                l_done = LT * KP;
+            }
+            for (int l0 = l_done; l0 < m; l0 += LT) {
                 __syncthreads();
-                // records before f come back from memory (written by earlier calls); record f
-                // itself is taken from this workgroup's registers
+                // records before f come back from memory (written by earlier calls)
 #pragma unroll
                 for (int x = 0; x < EPT; ++x) {
                     const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
@@ -620,23 +673,9 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                         uu[idx / D][e] = 0.0f;
                     }
                 }
-                if (f >= l0 && f < l0 + LT) {
-                    if (grp == 0) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            kh[f - l0][8 * sub + e] = k8[e];
-                    }
-                    if (tid < D)
-                        uu[f - l0][tid] = u_new;
-                }
+                inject_new(l0);
                 __syncthreads();
-                const int nl = min(LT, m - l0);
-                for (int l = 0; l < nl; ++l) {
-                    const float4 u = *reinterpret_cast<const float4 *>(&uu[l][4 * c4]);
-#pragma unroll
-                    for (int p = 0; p < NPASS; ++p)
-                        fma4(sreg[p], kh[l][rg + RPP * p], u);
-                }
+                apply_tile(l0);
             }
             float4 *sw = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
 #pragma unroll
