@@ -1,13 +1,17 @@
 // kvb -- KVBuffer-style Gated DeltaNet decoding, HIP kernels for gfx950 and the
 // C-ABI entry points declared in include/kvb.h.
 //
-// Work decomposition (all four calls): one 256-thread workgroup per (request b,
-// v-head h).  The committed state S0[dk][dv] (fp32, dv contiguous) is streamed
-// once with 16-byte loads: a thread owns 4 adjacent dv columns of the rows
-// rg, rg+RPP, rg+2*RPP, ... so a wave's load instruction covers whole
-// contiguous rows.  Everything a (b,h) unit needs besides the state -- the
-// buffered keys k_l, delta values u_l and cumulative log decays G_l (paper
-// App. A.1, the paragraph after Eq. 16) -- is a few KB and is staged through LDS.
+// Work decomposition (every kernel): one 256-thread workgroup per (request b,
+// v-head h); the committed state S0[dk][dv] (fp32, dv contiguous, 64 KB at
+// d = 128) is streamed exactly once per call.  Besides the state a unit needs
+// its buffered keys k_l, delta values u_l and cumulative log decays G_l (paper
+// App. A.1, the paragraph after Eq. 16), a few KB.
+//   kvb_step_kernel         decode (T = 1) and generic verify: vector ALUs; a thread owns
+//                           4 adjacent dv columns of 16 state rows (16-byte loads)
+//   kvb_verify_mfma_kernel  verify, bf16 / d = 128: matrix cores; a wave owns 32 dv columns
+//   kvb_flush_kernel        deferred state update as its own launch
+//   kvb_direct_mfma_kernel  short contexts, bf16 / d = 128: matrix cores throughout
+//   kvb_direct_kernel       short contexts, other types and head sizes
 //
 // Notation follows App. A.1: gamma_i = exp(G_i), Gamma_il = exp(G_i - G_l).
 
@@ -118,8 +122,8 @@ __device__ __forceinline__ void fma4(float4 &acc, float c, const float4 &x)
 // release ordering at device scope would make every workgroup write back and
 // invalidate its L2, which costs more than the kernel's whole memory traffic.
 //
-// The ticket is taken right after the read (take_ticket), so that its round trip
-// overlaps the workgroup's streaming, and is looked at only at the very end.
+// The ticket is taken once the workgroup's loads are in flight (take_ticket), so that its
+// round trip overlaps the streaming, and is looked at only at the very end.
 __device__ __forceinline__ int take_ticket(int32_t *word)
 {
     return __hip_atomic_fetch_add(word, TICKET_ONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
