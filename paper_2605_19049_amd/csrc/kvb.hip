@@ -228,6 +228,9 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     constexpr bool TAIL = WREC >= 64;
     constexpr int LT = 16;                 // records per LDS tile of the fused state update
     constexpr int EPT = LT * D / NT;
+    // state loads issued before the fill is known (the 64-record window keeps the records first:
+    // holding it across the state pass costs a workgroup per CU)
+    constexpr bool EARLY = TM == 1 && HAS_STATE && WREC <= 32;
     static_assert(!FUSE || (TM == 1 && HAS_STATE), "the fused update belongs to kvb_decode with a state");
 
     __shared__ __attribute__((aligned(16))) float sKs[TM][D];  // -gamma_i k_i (state-row weights for accU)
@@ -252,16 +255,6 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     const int s = a.slot[b];
     if (s < 0 || s >= a.st.n_slots)
         return;
-    const int f = a.st.fill[s] & FILL_MASK;
-    if (f + T > cap) {
-        if (tid == 0) {
-            if (a.st.status)
-                atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
-            if (a.advance)
-                publish_fill(&a.st.fill[s], a.Hv, f);
-        }
-        return;
-    }
 
     const int rg = tid / LPR, c4 = tid % LPR;
     const int grp = tid / GL, sub = tid % GL;
@@ -273,31 +266,75 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
     const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u + unit * cap * D);
 
-    // ---- 1. small loads --------------------------------------------------
-    // per-draft scalars (uniform)
-    float Gc[TM], bet[TM];
-    {
-        float run = f > 0 ? Gbuf[f - 1] : 0.0f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i < T) {
-                run += a.g[((size_t)b * T + i) * a.Hv + h];
-                bet[i] = a.beta[((size_t)b * T + i) * a.Hv + h];
-            } else {
-                bet[i] = 0.0f;
-            }
-            Gc[i] = run;
-        }
-    }
-    // All loads below are issued as raw bits from always-valid addresses (an index past
-    // the fill is clamped to record 0 and its value ignored), with no branch and no
-    // conversion in between, so nothing waits before the state tile is in flight.
+    // ---- 1. loads that need only the request index --------------------------
+    // All vector loads of this kernel are issued as raw bits from always-valid addresses (an
+    // index past the fill is clamped to record 0 and its value ignored), with no branch and
+    // no conversion in between, so nothing waits before the state tile is in flight.
     // new rows: each thread's 8-element slice of q_i, k_i (TM > 1: thread idx -> row idx / (D/8))
     const int nr_i = TM == 1 ? 0 : min(tid / (D / 8), T - 1);
     const int nr_e = TM == 1 ? sub : tid % (D / 8);
     const size_t nr_o = (((size_t)b * T + nr_i) * a.Hk + hk) * D + 8 * nr_e;
     const Raw8<TIn> q_raw = load_raw8(qin + nr_o);
     const Raw8<TIn> k_raw = load_raw8(kin + nr_o);
+    TIn v_raw[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + tid % D];
+
+    // ---- 2. the state tile goes in flight ------------------------------------
+    // Decoding one token (EARLY): the state's address needs the slot only, so its loads go out
+    // before the fill count is known.  Each dependent scalar load costs microseconds while the
+    // chip is streaming, and this takes one of them off the path to the first state byte.  The
+    // buffered records, whose addresses do need the fill, follow the state and are consumed
+    // after it.  The multi-row variants keep the records ahead of the state, since their
+    // dot-product phase is long enough to be worth hiding under the state's flight.
+    // (scheduling fences: the instruction scheduler must not reorder loads across them; the
+    // memory counter retires loads in issue order)
+    float4 sreg[NPASS];
+    auto issue_state = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            sreg[p] = load_state4<STREAM>(sp + (size_t)(rg + RPP * p) * LPR + c4);
+            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+        }
+    };
+    if constexpr (EARLY)
+        issue_state();
+
+    // per-row scalars (uniform); requested together with the fill, after the state loads,
+    // so that no scalar wait stands between the slot and the first state byte
+    float gnew[TM], bet[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const size_t o = ((size_t)b * T + min(i, T - 1)) * a.Hv + h;
+        gnew[i] = i < T ? a.g[o] : 0.0f;
+        bet[i] = i < T ? a.beta[o] : 0.0f;
+    }
+    const int f = a.st.fill[s] & FILL_MASK;
+    if (f + T > cap) {
+        if (tid == 0) {
+            if (a.st.status)
+                atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+            if (a.advance)
+                publish_fill(&a.st.fill[s], a.Hv, f);
+        }
+        return;
+    }
+    // cumulative log decay of the new rows (uniform)
+    float Gc[TM];
+    float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
+    auto finish_Gc = [&]() {
+        float run = G_prev;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            run += gnew[i];
+            Gc[i] = run;
+        }
+    };
+    if constexpr (!EARLY)
+        finish_Gc();
     // window of buffered records
     Raw8<TIn> kl_raw[KP];
     float Gl[KP];
@@ -314,24 +351,8 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         const int l = rg + RPP * j;
         ur[j] = up[(size_t)(l < f ? l : 0) * LPR + c4];
     }
-    TIn v_raw[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-        v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + tid % D];
-
-    // ---- 2. the state tile goes in flight ---------------------------------
-    // (scheduling fences: the instruction scheduler must not move a small load below
-    // the state loads, or a state load above them)
-    __builtin_amdgcn_sched_barrier(0);
-    float4 sreg[NPASS];
-    if constexpr (HAS_STATE) {
-        const float4 *sp = reinterpret_cast<const float4 *>(a.st.state + unit * D * D);
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            sreg[p] = load_state4<STREAM>(sp + (size_t)(rg + RPP * p) * LPR + c4);
-            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
-        }
-    }
+    if constexpr (HAS_STATE && !EARLY)
+        issue_state();
     __builtin_amdgcn_sched_barrier(0);
     // youngest memory operation of the wave: nothing waits for it before the very end
     int ticket = 0;
@@ -342,13 +363,20 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     float q8[8], k8[8];
     unpack8(q_raw, q8);
     unpack8(k_raw, k8);
+    float4 accU[TM], accO[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        accU[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        accO[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     if constexpr (TM == 1) {
-        const float gam = expf(Gc[0]);
+        // EARLY applies gamma after the sum over state rows (Gc comes back behind the state)
+        const float gw = EARLY ? 1.0f : expf(Gc[0]);
         if (grp == 0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                sKs[0][8 * sub + e] = -gam * k8[e];
-                sQs[0][8 * sub + e] = gam * q8[e];
+                sKs[0][8 * sub + e] = -gw * k8[e];
+                sQs[0][8 * sub + e] = gw * q8[e];
             }
         }
         float dqk = 0.0f;
@@ -359,6 +387,28 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         if (tid == 0) {
             cK[0][f] = 0.0f;
             cQ[0][f] = dqk;
+        }
+        if constexpr (EARLY) {
+            // the state rows are consumed first, in the order they were issued; the records
+            // (younger loads) are not touched before the last state row has been used
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const int row = rg + RPP * p;
+                fma4(accU[0], sKs[0][row], sreg[p]);
+                fma4(accO[0], sQs[0][row], sreg[p]);
+            }
+            // pins the sums (and everything derived from G_prev, a load younger than the
+            // state) to this point: pure arithmetic is otherwise free to drift across the fences
+            asm volatile("" : "+v"(accU[0].x), "+v"(accU[0].y), "+v"(accU[0].z), "+v"(accU[0].w),
+                              "+v"(accO[0].x), "+v"(accO[0].y), "+v"(accO[0].z), "+v"(accO[0].w),
+                              "+v"(G_prev));
+            __builtin_amdgcn_sched_barrier(0);
+            finish_Gc();
+            const float gam = expf(Gc[0]);
+            accU[0].x *= gam; accU[0].y *= gam; accU[0].z *= gam; accU[0].w *= gam;
+            accO[0].x *= gam; accO[0].y *= gam; accO[0].z *= gam; accO[0].w *= gam;
         }
 #pragma unroll
         for (int p = 0; p < KP; ++p) {
@@ -481,12 +531,6 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     __syncthreads();
 
     // ---- 4. accumulate over buffered records and state rows ----------------
-    float4 accU[TM], accO[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        accU[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        accO[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
 #pragma unroll
     for (int j = 0; j < UP; ++j) {
         const int l = rg + RPP * j;
@@ -510,7 +554,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             }
         }
     }
-    if constexpr (HAS_STATE) {
+    if constexpr (HAS_STATE && !EARLY) {
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             const int row = rg + RPP * p;
