@@ -1289,12 +1289,13 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     constexpr int NTW = ((WREC + TMX + 15) / 16 + NW - 1) / NW;  // tiles per wave held in registers
     constexpr int WQ = WREC / 4;                              // record quads held in registers
     constexpr bool TAIL = WREC >= 64;
+    constexpr bool EARLY = HAS_STATE && WREC <= 32;   // state loads issued before the fill is known
     static_assert(TMX == 8, "row m of W is draft m % 8");
 
     __shared__ __attribute__((aligned(16))) float sW[D][16];
     __shared__ __attribute__((aligned(16))) float cW[NTILE * 16][16];
     __shared__ __attribute__((aligned(16))) float fin[16][D];
-    __shared__ float sGc[NW][TMX];
+    __shared__ float sGc[TAIL ? NW : 1][TMX];   // per-wave table for the keys beyond the register window
 
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int lb = logical_block();
@@ -1308,12 +1309,6 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     const int s = a.slot[b];
     if (s < 0 || s >= a.st.n_slots)
         return;
-    const int f = a.st.fill[s] & FILL_MASK;
-    if (f + T > cap) {
-        if (tid == 0 && a.st.status)
-            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
-        return;
-    }
     const size_t unit = (size_t)s * a.Hv + h;
     const bf16_t *qin = static_cast<const bf16_t *>(a.q);
     const bf16_t *kin = static_cast<const bf16_t *>(a.k);
@@ -1323,29 +1318,9 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     const float *ub = a.st.buf_u + unit * cap * D;
 
     const int lm = lane % 16, lq = lane / 16;   // MFMA row/column index and k index of this lane
-    const int nrec = f + T;
-    const int ntile = (nrec + 15) / 16;
+    const int col2 = 32 * wave + 2 * lm;
 
-    // per-draft scalars.  Cumulative log decay of draft lane % 8, by a segmented scan, and a
-    // per-wave LDS table of all of them (looked up by draft index later; a register array
-    // indexed at run time would live in scratch memory, whose loads share the counter of the
-    // state loads).
-    float bet[TMX];
-#pragma unroll
-    for (int i = 0; i < TMX; ++i)
-        bet[i] = i < T ? a.beta[((size_t)b * T + i) * a.Hv + h] : 0.0f;
-    float Gmine = lane % 8 < T ? a.g[((size_t)b * T + lane % 8) * a.Hv + h] : 0.0f;
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {
-        const float t = __shfl_up(Gmine, off, 8);
-        if (lane % 8 >= off)
-            Gmine += t;
-    }
-    Gmine += f > 0 ? Gbuf[f - 1] : 0.0f;
-    if (lane < 8)
-        sGc[wave][lane] = Gmine;
-
-    // ---- 1. small loads: raw bits, clamped addresses, no branches -----------
+    // ---- 1. loads that need only the request index: raw bits, clamped addresses, no branches
     // row lm of W (draft lm % 8; k for lm < 8, q above), k-chunk lq of each 32-wide step
     const int wi = min(lm % 8, T - 1);
     const bf16_t *wrow = (lm < 8 ? kin : qin) + (((size_t)b * T + wi) * a.Hk + hk) * D + 8 * lq;
@@ -1353,6 +1328,47 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int st = 0; st < 4; ++st)
         wa[st] = *reinterpret_cast<const uint4 *>(wrow + 32 * st);
+
+    // ---- 2. the state: rows 4 st + lq, the wave's 32 columns -----------------
+    // EARLY: the state's address needs the slot only, so its loads go out before the fill is
+    // known and before the long scalar prologue; the records follow and are consumed after the
+    // state (the decay gamma_i of row i is then applied to the finished sum over state rows).
+    float2 sreg[D / 4];
+    auto issue_state = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        const float *sp = a.st.state + unit * D * D + col2;
+#pragma unroll
+        for (int st = 0; st < D / 4; ++st) {
+            const float2 *p = reinterpret_cast<const float2 *>(sp + (size_t)(4 * st + lq) * D);
+            if constexpr (STREAM) {
+                typedef float v2f __attribute__((ext_vector_type(2)));
+                const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+                sreg[st] = make_float2(t.x, t.y);
+            } else {
+                sreg[st] = *p;
+            }
+            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+        }
+    };
+    if constexpr (EARLY)
+        issue_state();
+
+    const int f = a.st.fill[s] & FILL_MASK;
+    if (f + T > cap) {
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+        return;
+    }
+    const int nrec = f + T;
+    const int ntile = (nrec + 15) / 16;
+
+    // ---- 3. loads that need the fill ------------------------------------------
+    // per-draft scalars of draft lane % 8, one vector load each (a scalar load per draft costs
+    // a round trip each while the chip is streaming)
+    const size_t go = ((size_t)b * T + min(lane % 8, T - 1)) * a.Hv + h;
+    float g_raw = a.g[go];
+    float beta_mine = a.beta[go];
+    float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
     // keys of this wave's tiles (buffered first, then the new ones)
     uint4 kt[NTW][4];
     float Gn[NTW];
@@ -1368,7 +1384,6 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     }
     // buffered delta values: quad sq = records 4 sq .. 4 sq + 3, this lane: record 4 sq + lq,
     // columns 32 wave + 2 lm, + 1
-    const int col2 = 32 * wave + 2 * lm;
     float2 uq[WQ];
 #pragma unroll
     for (int sq = 0; sq < WQ; ++sq) {
@@ -1381,28 +1396,48 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int i = 0; i < TMX; ++i)
         v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + colf];
-
-    // ---- 2. the state: rows 4 st + lq, the wave's 32 columns -----------------
+    if constexpr (HAS_STATE && !EARLY)
+        issue_state();
     __builtin_amdgcn_sched_barrier(0);
-    float2 sreg[D / 4];
-    if constexpr (HAS_STATE) {
-        const float *sp = a.st.state + unit * D * D + col2;
+
+    // Cumulative log decays and betas of the drafts as wave-uniform values read from the lanes
+    // that loaded them.  Whatever a lane needs by a draft index of its own is selected here,
+    // while the running sum is in a register: an array indexed at run time would live in
+    // scratch memory, whose loads share the counter of the state loads.
+    float bet[TMX];
+    float GcRow[4];      // of the draft of accumulator row 4 lq + v: draft v (lq even) or 4 + v (lq odd)
+    float GcLm = 0.0f;   // of draft lm % 8 (the row of W this lane loaded)
+    float GcTid = 0.0f;  // of draft tid (the lane that stores it)
+    float GcKey[NTW];    // of the new key this lane holds in window tile x, if it holds one
 #pragma unroll
-        for (int st = 0; st < D / 4; ++st) {
-            const float2 *p = reinterpret_cast<const float2 *>(sp + (size_t)(4 * st + lq) * D);
-            if constexpr (STREAM) {
-                typedef float v2f __attribute__((ext_vector_type(2)));
-                const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
-                sreg[st] = make_float2(t.x, t.y);
-            } else {
-                sreg[st] = *p;
-            }
-            __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+    for (int x = 0; x < NTW; ++x)
+        GcKey[x] = 0.0f;
+    auto finish_Gc = [&]() {
+        float run = G_prev;
+#pragma unroll
+        for (int i = 0; i < TMX; ++i) {
+            const float gi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g_raw), i));
+            bet[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, beta_mine), i));
+            run += i < T ? gi : 0.0f;
+            if (i < 4)
+                GcRow[i] = run;
+            else
+                GcRow[i - 4] = lq % 2 ? run : GcRow[i - 4];
+            GcLm = lm % 8 == i ? run : GcLm;
+            GcTid = tid == i ? run : GcTid;
+#pragma unroll
+            for (int x = 0; x < NTW; ++x)
+                GcKey[x] = 16 * (wave + NW * x) + lm - f == i ? run : GcKey[x];
+            if (TAIL && lane == 0)
+                sGc[wave][i] = run;
         }
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    };
+    if constexpr (!EARLY)
+        finish_Gc();
 
-    // ---- 3. stage 1: weights of the state rows, decayed dot products ----------
+    // ---- 4. weights of the state rows ------------------------------------------
+    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    const bool live = lm % 8 < T;
     {
         // the chunk this lane holds for step == wave covers state rows 32 wave + 8 lq .. + 7
         float x[8];
@@ -1415,14 +1450,46 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
             for (int e = 0; e < 8; ++e)
                 x[e] = wave == st ? y[e] : x[e];
         }
-        const bool live = lm % 8 < T;
-        const float gam = live ? expf(Gmine) : 0.0f;   // lm % 8 == lane % 8
+        float gam;
+        if constexpr (EARLY)
+            gam = live ? 1.0f : 0.0f;
+        else
+            gam = live ? expf(GcLm) : 0.0f;
         const float sg = lm < 8 ? -gam : gam;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             sW[32 * wave + 8 * lq + e][lm] = sg * x[e];
     }
-    auto key_tile = [&](int tile, const uint4(&kk)[4], float Gx) {
+    auto state_rows = [&]() {
+#pragma unroll
+        for (int st = 0; st < D / 4; ++st) {
+            const float aw = sW[4 * st + lq][lm];
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].y, acc1, 0, 0, 0);
+        }
+    };
+    if constexpr (EARLY) {
+        __syncthreads();   // sW complete
+        __builtin_amdgcn_sched_barrier(0);
+        state_rows();
+        // pins the sums, and whatever derives from the loads younger than the state, to this
+        // point: pure arithmetic is otherwise free to drift across the fences
+        asm volatile("" : "+v"(acc0), "+v"(acc1), "+v"(G_prev), "+v"(g_raw), "+v"(beta_mine));
+        __builtin_amdgcn_sched_barrier(0);
+        finish_Gc();
+        // acc*[v] is row m = 4 lq + v = draft m % 8: apply its gamma
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = (4 * lq + v) % 8;
+            const float gam = i < T ? expf(GcRow[v]) : 0.0f;
+            acc0[v] *= gam;
+            acc1[v] *= gam;
+        }
+    }
+
+    // ---- 5. stage 1: decayed dot products with every buffered and new key -------
+    // Gkey: cumulative log decay of key n of the tile (a buffered one from memory, a new one from above)
+    auto key_tile = [&](int tile, const uint4(&kk)[4], float Gkey) {
         f32x4_t c1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -1430,14 +1497,13 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
                                                          __builtin_bit_cast(bf16x8_t, kk[st]), c1, 0, 0, 0);
         // this lane: rows m = 4 lq + v of W against key n
         const int n = 16 * tile + lm;
-        const float Gkey = n < f ? Gx : sGc[wave][min(max(n - f, 0), TMX - 1)];
         float o[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int m = 4 * lq + v, i = m % 8;
             const bool isq = m >= 8;
             const bool ok = i < T && n < nrec && (n < f || (isq ? n - f <= i : n - f < i));
-            const float w = ok ? expf(sGc[wave][i] - Gkey) : 0.0f;
+            const float w = ok ? expf(GcRow[v] - Gkey) : 0.0f;
             o[v] = (isq ? w : -w) * c1[v];
         }
         *reinterpret_cast<float4 *>(&cW[n][4 * lq]) = make_float4(o[0], o[1], o[2], o[3]);
@@ -1446,7 +1512,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     for (int x = 0; x < NTW; ++x) {
         const int tile = wave + NW * x;
         if (tile < ntile)
-            key_tile(tile, kt[x], Gn[x]);
+            key_tile(tile, kt[x], 16 * tile + lm < f ? Gn[x] : GcKey[x]);
     }
     for (int tile = wave + NW * NTW; TAIL && tile < ntile; tile += NW) {   // keys beyond the register window
         const int n = 16 * tile + lm;
@@ -1456,12 +1522,12 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             kk[st] = *reinterpret_cast<const uint4 *>(kp + 8 * lq + 32 * st);
-        key_tile(tile, kk, Gbuf[n < f ? n : 0]);
+        const float Gb = Gbuf[n < f ? n : 0];
+        key_tile(tile, kk, n < f ? Gb : sGc[wave][min(max(n - f, 0), TMX - 1)]);
     }
     __syncthreads();
 
-    // ---- 4. stage 2: records, then state rows, on the fp32 matrix cores ------
-    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    // ---- 6. stage 2 on the fp32 matrix cores: records (and, if not yet done, state rows)
     const int nquad = (f + 3) / 4;
 #pragma unroll
     for (int sq = 0; sq < WQ; ++sq) {
@@ -1479,14 +1545,8 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.x : 0.0f, acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.y : 0.0f, acc1, 0, 0, 0);
     }
-    if constexpr (HAS_STATE) {
-#pragma unroll
-        for (int st = 0; st < D / 4; ++st) {
-            const float aw = sW[4 * st + lq][lm];
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].x, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].y, acc1, 0, 0, 0);
-        }
-    }
+    if constexpr (HAS_STATE && !EARLY)
+        state_rows();
     // acc*[v] = row m = 4 lq + v, column col2 (+1)
 #pragma unroll
     for (int v = 0; v < 4; ++v)
@@ -1494,22 +1554,57 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     __syncthreads();
 
     // ---- 5. the T new rows among themselves; results ---------------------------
+    // (all loads are consumed before the first store: the memory counter also counts stores,
+    // and a wait for a late load inside the loop would wait for the stores of earlier drafts)
+    float vf[TMX];
+#pragma unroll
+    for (int i = 0; i < TMX; ++i) {
+        vf[i] = to_f32(v_raw[i]);
+        asm volatile("" : "+v"(vf[i]));
+    }
     if (lane < 32) {
+        // every LDS value of the substitution is fetched up front (independent reads, one
+        // round trip for all) rather than one by one along the serial chain
+        float fu[TMX], fo[TMX], ck[TMX][TMX], cq[TMX][TMX];
+#pragma unroll
+        for (int i = 0; i < TMX; ++i) {
+            if (i < T) {   // uniform
+                fu[i] = fin[i][colf];
+                fo[i] = fin[8 + i][colf];
+#pragma unroll
+                for (int j = 0; j <= i; ++j) {
+                    ck[i][j] = cW[f + j][i];       // K rows are stored negated
+                    cq[i][j] = cW[f + j][8 + i];
+                }
+            } else {
+                fu[i] = fo[i] = 0.0f;
+#pragma unroll
+                for (int j = 0; j <= i; ++j)
+                    ck[i][j] = cq[i][j] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TMX; ++i) {
+            asm volatile("" : "+v"(fu[i]), "+v"(fo[i]));
+#pragma unroll
+            for (int j = 0; j <= i; ++j)
+                asm volatile("" : "+v"(ck[i][j]), "+v"(cq[i][j]));
+        }
         float uprev[TMX];
 #pragma unroll
         for (int i = 0; i < TMX; ++i) {
             if (i < T) {
-                float acc = to_f32(v_raw[i]) + fin[i][colf];
-                float ao = fin[8 + i][colf];
+                float acc = vf[i] + fu[i];
+                float ao = fo[i];
 #pragma unroll
                 for (int j = 0; j < TMX; ++j) {
                     if (j < i) {
-                        acc = fmaf(cW[f + j][i], uprev[j], acc);     // K rows are stored negated
-                        ao = fmaf(cW[f + j][8 + i], uprev[j], ao);
+                        acc = fmaf(ck[i][j], uprev[j], acc);
+                        ao = fmaf(cq[i][j], uprev[j], ao);
                     }
                 }
                 const float ui = bet[i] * acc;
-                ao = fmaf(cW[f + i][8 + i], ui, ao);
+                ao = fmaf(cq[i][i], ui, ao);
                 uprev[i] = ui;
                 a.out[(((size_t)b * T + i) * a.Hv + h) * D + colf] = a.scale * ao;
                 a.st.buf_u[(unit * cap + f + i) * D + colf] = ui;
@@ -1517,7 +1612,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         }
     }
     if (tid < T)
-        a.st.buf_G[unit * cap + f + tid] = Gmine;   // tid < 8: lane % 8 == tid
+        a.st.buf_G[unit * cap + f + tid] = GcTid;
     if (h % r == 0 && wave == 0 && lm < T) {   // lanes holding k rows store them
         bf16_t *kw = static_cast<bf16_t *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f + lm) * D + 8 * lq;
 #pragma unroll
