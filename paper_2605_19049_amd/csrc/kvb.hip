@@ -1029,7 +1029,7 @@ __device__ __forceinline__ f32x4_t gram16(const bf16_t *arow, const bf16_t *brow
     return c;
 }
 
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void kvb_direct_mfma_kernel(
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void kvb_direct_mfma_kernel(
     const DirectArgs a)
 {
     constexpr int D = 128;
@@ -1042,13 +1042,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // One LDS region, used twice: first the staged K and Q rows (bf16), then, once every
     // raw Gram tile sits in registers, the weighted tiles in A-form (one float4 per lane):
     // -N_de (d > e), M_de (d >= e), T_d.
-    constexpr int STAGE_BYTES = 2 * LM * GS * 2;
+    constexpr int STAGE_BYTES = LM * GS * 2;
     constexpr int TILE_BYTES = (2 * NLOW + NB) * 64 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
     __shared__ float sG[LM];
     __shared__ float sB[LM];
     bf16_t *sK = reinterpret_cast<bf16_t *>(region);
-    bf16_t *sQ = sK + LM * GS;
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NLOW;
     float4(*tT)[64] = tM + NLOW;
@@ -1086,7 +1085,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // ---- all global loads of the workgroup, issued together ---------------------
     // K and Q rows, 16 bytes per thread and pass (pass p = rows 16 p .. 16 p + 15)
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    u32x4_t kst[NB], qst[NB];
+    u32x4_t kst[NB];
     const int srow = tid / 16, sc8 = tid % 16;
     // (uniform 64-bit base + 32-bit per-lane offset keeps the address arithmetic out of the VGPRs)
     const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
@@ -1097,24 +1096,31 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
         const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
         kst[p] = u32x4_t{0u, 0u, 0u, 0u};
-        qst[p] = kst[p];
-        if (p < nb) {   // uniform
+        if (p < nb)   // uniform
             kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
-            qst[p] = *reinterpret_cast<const u32x4_t *>(qbase + o);
+    }
+    // Q is not staged: the waves read the rows of their q.k tiles straight from memory in the
+    // operand layout of the matrix instruction (row 16 d + c16, k = 8 lq + 32 step); a block of
+    // 16 query rows is 4 KB and is shared by at most 4 tiles, so the repeats hit in the caches
+    // and the LDS footprint is that of K alone (5 workgroups per CU instead of 4).
+    // Tiles are dealt round-robin: t = wave + 4 n; t < 6 are k.k pairs, the rest q.k pairs.
+    constexpr uint32_t PDB = pack2(1, 2, 2, 3, 3, 3, 0, 1, 1, 2, 2, 2, 3, 3, 3, 3);
+    constexpr uint32_t PEB = pack2(0, 0, 1, 0, 1, 2, 0, 0, 1, 0, 1, 2, 0, 1, 2, 3);
+    auto PD = [](int t) { return (int)((PDB >> (2 * t)) & 3u); };
+    auto PE = [](int t) { return (int)((PEB >> (2 * t)) & 3u); };
+    u32x4_t qop[3][4];   // n = 1 (waves 2, 3 only), 2, 3
+#pragma unroll
+    for (int n = 1; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t);
+        const uint32_t o = (uint32_t)min(16 * d + c16, L - 1) * qk_stride + 8 * lq;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            qop[n - 1][st] = u32x4_t{0u, 0u, 0u, 0u};
+            if (t >= 6 && d < nb)   // uniform
+                qop[n - 1][st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
         }
     }
-    // v in B-form: rows 16 d + 4 lq + v, this lane's two adjacent columns 32 wave + 2 c16, + 1
     const int col2 = 32 * wave + 2 * c16;
-    uint32_t v_raw[NB][4];
-#pragma unroll
-    for (int d = 0; d < NB; ++d)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            v_raw[d][v] = 0u;
-            if (d < nb)   // uniform
-                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
-                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
-        }
     // cumulative log decay (inclusive scan over the wave) and beta
     if (wave == 0) {
         float gv = lane < L ? a.g[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
@@ -1136,7 +1142,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     for (int p = 0; p < NB; ++p) {
         if (p < nb) {   // uniform
             *reinterpret_cast<u32x4_t *>(sK + (16 * p + srow) * GS + 8 * sc8) = kst[p];
-            *reinterpret_cast<u32x4_t *>(sQ + (16 * p + srow) * GS + 8 * sc8) = qst[p];
             if (h % r == 0 && 16 * p + srow < L)
                 *reinterpret_cast<u32x4_t *>(kb + (size_t)(16 * p + srow) * D + 8 * sc8) = kst[p];
         }
@@ -1144,12 +1149,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     __syncthreads();
 
     // ---- raw Gram tiles: this wave's diagonal k.k tile and its share of the others ----
-    // off-diagonal k.k pairs (d > e): 6; q.k pairs (d >= e): 10; dealt round-robin
+    // off-diagonal k.k pairs (d > e): 6; q.k pairs (d >= e): 10
     // (two bits per entry, packed: a table indexed by the wave number would live in scratch)
-    constexpr uint32_t PDB = pack2(1, 2, 2, 3, 3, 3, 0, 1, 1, 2, 2, 2, 3, 3, 3, 3);
-    constexpr uint32_t PEB = pack2(0, 0, 1, 0, 1, 2, 0, 0, 1, 0, 1, 2, 0, 1, 2, 3);
-    auto PD = [](int t) { return (int)((PDB >> (2 * t)) & 3u); };
-    auto PE = [](int t) { return (int)((PEB >> (2 * t)) & 3u); };
     f32x4_t gdiag = {0.f, 0.f, 0.f, 0.f};
     if (wave < nb)
         gdiag = gram16<GS>(sK + (16 * wave + c16) * GS, sK + (16 * wave + c16) * GS, lq);
@@ -1158,10 +1159,36 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     for (int n = 0; n < 4; ++n) {
         const int t = wave + NW * n, d = PD(t), e = PE(t);
         gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (d < nb)   // uniform
-            gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, (t < 6 ? sK : sQ) + (16 * d + c16) * GS, lq);
+        if (d < nb) {   // uniform
+            if (t < 6) {
+                gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
+            } else if (n > 0) {   // t >= 6 implies n >= 1
+                const bf16_t *arow = sK + (16 * e + c16) * GS;
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
+                    gsh[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, qop[n > 0 ? n - 1 : 0][st]),
+                        gsh[n], 0, 0, 0);
+                }
+            }
+        }
     }
     __syncthreads();   // every wave is done with the staged rows: the region now takes the tiles
+
+    // v in B-form: rows 16 d + 4 lq + v, this lane's two adjacent columns 32 wave + 2 c16, + 1.
+    // Requested only now, when the registers of the staged rows are free again; the values
+    // are not needed before the substitution, two phases further down.
+    uint32_t v_raw[NB][4];
+#pragma unroll
+    for (int d = 0; d < NB; ++d)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            v_raw[d][v] = 0u;
+            if (d < nb)   // uniform
+                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+        }
 
     // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
 #pragma unroll
@@ -1606,10 +1633,20 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
                 const float ui = bet[i] * acc;
                 ao = fmaf(cq[i][i], ui, ao);
                 uprev[i] = ui;
-                a.out[(((size_t)b * T + i) * a.Hv + h) * D + colf] = a.scale * ao;
-                a.st.buf_u[(unit * cap + f + i) * D + colf] = ui;
+                fin[i][colf] = ui;                 // a lane overwrites only what it has read itself
+                fin[8 + i][colf] = a.scale * ao;
             }
         }
+    }
+    __syncthreads();
+    // results leave as whole 512-byte rows, 16 bytes per lane: T rows of u, then T rows of out
+    for (int idx = tid; idx < 2 * T * (D / 4); idx += NT) {
+        const int rr = idx / (D / 4), c4 = idx % (D / 4);
+        const bool is_u = rr < T;
+        const int i = is_u ? rr : rr - T;
+        const float4 val = *reinterpret_cast<const float4 *>(&fin[is_u ? i : 8 + i][4 * c4]);
+        float *dst = is_u ? a.st.buf_u + (unit * cap + f + i) * D : a.out + (((size_t)b * T + i) * a.Hv + h) * D;
+        *reinterpret_cast<float4 *>(dst + 4 * c4) = val;
     }
     if (tid < T)
         a.st.buf_G[unit * cap + f + tid] = GcTid;
