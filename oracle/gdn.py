@@ -103,3 +103,58 @@ def kvb_direct_expected(q, k, v, g, beta, lens, scale=1.0):
     S0 = np.zeros((B, Hv, dk, dv))
     o, u, S_end, _ = gdn_sequence(S0, q, k, v, g, beta, scale, lens=lens)
     return o, u, S_end
+
+
+def tree_paths(parent):
+    """Root paths of a draft tree.  parent [B,T] with parent[b,i] in {-1, 0..i-1} (-1: the
+    node follows the last committed token).  Returns (idx [B,T,T], plen [B,T]): the nodes of
+    the path that ends in node i, oldest first, padded with node i itself."""
+    parent = np.asarray(parent)
+    B, T = parent.shape
+    idx = np.zeros((B, T, T), np.int64)
+    plen = np.zeros((B, T), np.int32)
+    for b in range(B):
+        for i in range(T):
+            path, n = [], i
+            while n >= 0:
+                assert n < T and parent[b, n] < n, "parent indices must precede their children"
+                path.append(n)
+                n = int(parent[b, n])
+            path.reverse()
+            plen[b, i] = len(path)
+            idx[b, i, :len(path)] = path
+            idx[b, i, len(path):] = i
+    return idx, plen
+
+
+def kvb_verify_tree_expected(S, q, k, v, g, beta, parent, accepted_leaf=None, scale=1.0):
+    """Verification of tree-shaped drafts (Sec. 3.3 with the mask M of App. A.1: a draft
+    sees the committed context and its own ancestors only).  Node i's output and delta value
+    are what the recurrence yields at the end of the root path of node i, started from a
+    scratch copy of the true state S; every path is simply fed to the recurrence.
+    accepted_leaf [B] (-1 = nothing accepted): the state then advances along the root path of
+    that node only (Eq. 8).  Returns (o [B,T,Hv,dv], u [B,T,Hv,dv], S_acc)."""
+    S = _f64(S)
+    q, k, v, g, beta = map(_f64, (q, k, v, g, beta))
+    B, T = g.shape[:2]
+    idx, plen = tree_paths(parent)
+    bb = np.arange(B)[:, None, None]
+    # one "request" per (b, node): the tokens of its root path, in order
+    def along(x):
+        return x[bb, idx].reshape((B * T, T) + x.shape[2:])
+    Sx = np.repeat(S, T, axis=0)
+    o_p, u_p, _, _ = gdn_sequence(Sx, along(q), along(k), along(v), along(g), along(beta), scale,
+                                  lens=plen.reshape(-1))
+    last = (plen.reshape(-1) - 1)
+    rows = np.arange(B * T)
+    o = o_p[rows, last].reshape((B, T) + o_p.shape[2:])
+    u = u_p[rows, last].reshape((B, T) + u_p.shape[2:])
+    S_acc = S.copy()
+    if accepted_leaf is not None:
+        leaf = np.asarray(accepted_leaf)
+        sel = np.where(leaf >= 0, leaf, 0)
+        ib = idx[np.arange(B), sel]                         # [B,T] path of the accepted leaf
+        ln = np.where(leaf >= 0, plen[np.arange(B), sel], 0).astype(np.int32)
+        b1 = np.arange(B)[:, None]
+        _, _, S_acc, _ = gdn_sequence(S, q[b1, ib], k[b1, ib], v[b1, ib], g[b1, ib], beta[b1, ib], scale, lens=ln)
+    return o, u, S_acc

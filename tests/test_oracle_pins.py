@@ -272,3 +272,69 @@ def test_planted_mistakes_are_caught(oracle):
     np.testing.assert_allclose(recur(), O, rtol=1e-10, atol=1e-11)
     for kw in ({"transpose": True}, {"no_gate": True}, {"pre_read": True}):
         assert np.abs(recur(**kw) - O).max() > 1e-3, kw
+
+
+# ------------------------------------------------------------ tree-shaped drafts
+def tree_matrix_form(S0, Q, K, V, g, beta, parent):
+    """The masked matrix form for one head (App. A.1: M_ij != 0 iff j is a prefix token of i,
+    gamma_t = product of alpha over Par(t)), on top of a committed state S0 as in Eq. 15.
+    M is built from the parent pointers; everything else is the dense inverse as printed."""
+    m = Q.shape[0]
+    M = np.zeros((m, m))
+    G = np.zeros(m)
+    for i in range(m):
+        n = i
+        while n >= 0:
+            M[i, n] = 1.0
+            G[i] += g[n]
+            n = parent[n]
+    gam = np.exp(G)
+    Gam = M * (gam[:, None] / gam[None, :])
+    A = np.linalg.inv(np.eye(m) + np.tril(beta[:, None] * (Gam * (K @ K.T)), -1))
+    U = A @ (beta[:, None] * (V - gam[:, None] * (K @ S0)))
+    O = gam[:, None] * (Q @ S0) + ((Q @ K.T) * Gam) @ U
+    return O, U, gam, Gam
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_tree_drafts_equal_the_masked_matrix_form(oracle, seed):
+    """Every draft of a random tree, against the dense-inverse form with the ancestor mask;
+    the committed state after accepting a leaf, against S0 advanced by that root path."""
+    B, T, Hk, Hv, dk, dv = 3, 7, 1, 2, 6, 5
+    S0, q, k, v, g, beta = _inputs(seed, B, T, Hk, Hv, dk, dv)
+    rng = np.random.default_rng(seed)
+    parent = np.stack([[int(rng.integers(-1, i)) for i in range(T)] for _ in range(B)])
+    leaf = np.array([T - 1, 2, -1])
+    o, u, S_acc = oracle.kvb_verify_tree_expected(S0, q, k, v, g, beta, parent, accepted_leaf=leaf)
+    for b in range(B):
+        for h in range(Hv):
+            O, U, gam, Gam = tree_matrix_form(S0[b, h], q[b, :, 0], k[b, :, 0], v[b, :, h], g[b, :, h],
+                                              beta[b, :, h], parent[b])
+            np.testing.assert_allclose(O, o[b, :, h], rtol=1e-10, atol=1e-11)
+            np.testing.assert_allclose(U, u[b, :, h], rtol=1e-10, atol=1e-11)
+            if leaf[b] >= 0:   # Eq. 8 / last line of Eq. 16 over the accepted path only
+                L = leaf[b]
+                want = gam[L] * S0[b, h] + (k[b, :, 0] * Gam[L][:, None]).T @ U
+                np.testing.assert_allclose(want, S_acc[b, h], rtol=1e-10, atol=1e-11)
+            else:
+                assert np.array_equal(S_acc[b, h], S0[b, h])
+
+
+def test_tree_special_cases(oracle):
+    """A chain is sequential verification; a star is T independent single-token steps."""
+    B, T, Hk, Hv, dk, dv = 2, 5, 1, 2, 6, 5
+    S0, q, k, v, g, beta = _inputs(24, B, T, Hk, Hv, dk, dv)
+    chain = np.tile(np.arange(T) - 1, (B, 1))
+    o_c, u_c, S_c = oracle.kvb_verify_tree_expected(S0, q, k, v, g, beta, chain, accepted_leaf=np.array([3, 0]))
+    o_s, u_s, S_s = oracle.kvb_verify_expected(S0, q, k, v, g, beta, np.array([4, 1], dtype=np.int32))
+    assert np.array_equal(o_c, o_s) and np.array_equal(u_c, u_s) and np.array_equal(S_c, S_s)
+    star = np.full((B, T), -1)
+    o_t, u_t, _ = oracle.kvb_verify_tree_expected(S0, q, k, v, g, beta, star)
+    for b in range(B):
+        for h in range(Hv):
+            for t in range(T):   # one step of Eq. 11-12 written out
+                S = np.exp(g[b, t, h]) * S0[b, h]
+                uu = beta[b, t, h] * (v[b, t, h] - k[b, t, 0] @ S)
+                oo = q[b, t, 0] @ (S + np.outer(k[b, t, 0], uu))
+                np.testing.assert_allclose(uu, u_t[b, t, h], rtol=1e-12, atol=1e-13)
+                np.testing.assert_allclose(oo, o_t[b, t, h], rtol=1e-12, atol=1e-13)
