@@ -171,6 +171,13 @@ def time_other_paths(torch, kvb, synth, traffic, reps=20):
     byt = sum(traffic.total(traffic.verify_rw(traffic.KVB, int(f), w.T)) for f in fills) * w.Hv
     res["kvb_verify"] = {"workload": "spec_verify B=128 T=4 fill~U(0,15)", "us": sec * 1e6,
                          "algorithmic_GBps": byt / sec / 1e9, "draft_tokens_per_s": w.B * w.T / sec}
+    # the same drafts as trees (a random 4-node tree per request); same bytes
+    parent = torch.from_numpy(synth.draft_trees(rng, w.B, w.T, "random")).cuda()
+    call = kvb.bind("kvb_verify_tree", sh, st, slot, w.T, parent, tok["q"], tok["k"], tok["v"], tok["g"],
+                    tok["beta"], out, torch.cuda.current_stream().cuda_stream)
+    sec = timed(call, reps)
+    res["kvb_verify_tree"] = {"workload": "spec_verify B=128, random trees of 4 drafts, fill~U(0,15)", "us": sec * 1e6,
+                              "algorithmic_GBps": byt / sec / 1e9, "draft_tokens_per_s": w.B * w.T / sec}
     del ds
 
     # direct: B=256, L ~U(1,64)

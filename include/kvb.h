@@ -57,8 +57,10 @@ extern "C" {
 #define KVB_STORE_STREAM   1
 #define KVB_STORE_RESIDENT 2
 
-/* bit set in status[slot] when a call would have overrun that request's buffer */
+/* bits set in status[slot]: a call would have overrun that request's buffer; a draft tree or
+ * an accepted path handed to kvb_verify_tree / kvb_compact was not well formed */
 #define KVB_STATUS_OVERFLOW 1
+#define KVB_STATUS_BADPATH  2
 
 typedef struct kvb_shape {
     int32_t B;         /* requests in this call (0 = no-op)                                */
@@ -151,6 +153,39 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
 int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
                const void *q, const void *k, const void *v,
                const float *g, const float *beta, void *out, void *stream);
+
+/*
+ * kvb_verify_tree -- kvb_verify for drafts that form a tree (Sec. 3.3: the mask M and the
+ * prefix set Par(t) of App. A.1 admit any draft structure; the figure of Sec. 3.3 accepts
+ * drafts 0 and 2 of three).  Draft i continues the committed context and then exactly its
+ * ancestors among the T drafts: its decay, its delta value and its output are those of the
+ * root path that ends in i.  With parent[b][i] = i - 1 this is kvb_verify.
+ *   parent  device int32 [B, T]: parent[b][i] in {-1, 0 .. i-1}; -1 = the draft follows the last
+ *           committed token.  Parents precede their children.  An entry outside that range is
+ *           taken as -1 and status[slot] gets KVB_STATUS_BADPATH.  T = 1: not read.
+ * Everything else as kvb_verify: record f + i holds draft i (its G is cumulative along its own
+ * path), fill and state are untouched.  Committing an accepted root path is kvb_compact followed
+ * by kvb_flush(accepted = path_len).
+ */
+int kvb_verify_tree(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
+                    const int32_t *parent, const void *q, const void *k, const void *v,
+                    const float *g, const float *beta, void *out, void *stream);
+
+/*
+ * kvb_compact -- makes the accepted drafts of a tree a prefix of the T new records (Sec. 3.3,
+ * Eq. 8: only accepted tokens reach the state).  For request b the records at f + path[b][j]
+ * move to f + j, j = 0 .. path_len[b]-1; the caller then commits them with
+ * kvb_flush(accepted = path_len, ...).  Neither fill nor state changes here.
+ *   T         the T of the preceding kvb_verify_tree
+ *   path      device int32 [B, T]: the accepted root path, oldest draft first, strictly increasing
+ *             node indices in 0 .. T-1 (the caller passes a path of the tree; only its order and
+ *             range are checked)
+ *   path_len  device int32 [B]: 0 .. T accepted drafts
+ * A path that is not increasing, a length outside 0..T, or f + T > cap leaves the request's
+ * records as they are and sets KVB_STATUS_BADPATH.
+ */
+int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
+                const int32_t *path, const int32_t *path_len, void *stream);
 
 /*
  * kvb_direct -- state-free computation of a whole short context from its keys

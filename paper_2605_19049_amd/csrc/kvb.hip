@@ -182,6 +182,11 @@ struct StepArgs {
     int32_t advance;    // 1: decode (fill += T after the step); 0: verify (fill untouched)
     int32_t threshold;  // fused decode + flush only: fold the buffer into the state once it holds this many
     int32_t stream_state;  // non-temporal state loads
+    // kvb_verify_tree: parent[b][i] in {-1, 0..i-1} of draft i.  When `tree` is 0 the drafts are
+    // a chain and `parent` points at some other readable array of at least B*T words (its
+    // values are ignored), so that the kernels can load it without a branch.
+    const int32_t *parent;
+    int32_t tree;
 };
 
 // ---------------------------------------------------------------------------
@@ -306,11 +311,17 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     // per-row scalars (uniform); requested together with the fill, after the state loads,
     // so that no scalar wait stands between the slot and the first state byte
     float gnew[TM], bet[TM];
+    int par[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const size_t o = ((size_t)b * T + min(i, T - 1)) * a.Hv + h;
         gnew[i] = i < T ? a.g[o] : 0.0f;
         bet[i] = i < T ? a.beta[o] : 0.0f;
+        par[i] = i - 1;
+        if constexpr (TM > 1) {
+            const int pl = a.parent[(size_t)b * T + min(i, T - 1)];
+            par[i] = a.tree ? pl : i - 1;
+        }
     }
     const int f = a.st.fill[s] & FILL_MASK;
     if (f + T > cap) {
@@ -323,15 +334,30 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         return;
     }
     // cumulative log decay of the new rows (uniform)
+    // Gc[i]: cumulative log decay of new row i along its own root path (a chain unless the
+    // drafts form a tree); anc[i]: bit j set iff new row j is a strict ancestor of row i.
+    // A parent index that does not precede its child is taken as -1 and flagged.
     float Gc[TM];
+    int anc[TM];
     float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
     auto finish_Gc = [&]() {
-        float run = G_prev;
+        bool bad = false;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            run += gnew[i];
-            Gc[i] = run;
+            float base = G_prev;
+            int am = 0;
+            bad = bad || (i < T && (par[i] < -1 || par[i] >= i));
+#pragma unroll
+            for (int j = 0; j < i; ++j) {
+                const bool is_parent = par[i] == j;
+                base = is_parent ? Gc[j] : base;
+                am = is_parent ? (anc[j] | (1 << j)) : am;
+            }
+            Gc[i] = base + gnew[i];
+            anc[i] = am;
         }
+        if (TM > 1 && bad && tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_BADPATH);
     };
     if constexpr (!EARLY)
         finish_Gc();
@@ -517,13 +543,15 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             dq = group_sum<GL>(dq);
             if (sub == 0) {
                 float Gi = 0.0f, Gj = 0.0f;
+                int ai = 0;
 #pragma unroll
                 for (int x = 0; x < TM; ++x) {
-                    if (x == i) Gi = Gc[x];
+                    if (x == i) { Gi = Gc[x]; ai = anc[x]; }
                     if (x == j) Gj = Gc[x];
                 }
-                const float w = j <= i ? expf(Gi - Gj) : 0.0f;
-                cK[i][f + j] = j < i ? w * dkk : 0.0f;
+                const bool above = (ai >> j) & 1;   // row j is a strict ancestor of row i
+                const float w = (above || j == i) ? expf(Gi - Gj) : 0.0f;
+                cK[i][f + j] = above ? w * dkk : 0.0f;
                 cQ[i][f + j] = w * dq;
             }
         }
@@ -1395,6 +1423,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     const size_t go = ((size_t)b * T + min(lane % 8, T - 1)) * a.Hv + h;
     float g_raw = a.g[go];
     float beta_mine = a.beta[go];
+    int par_raw = a.parent[(size_t)b * T + min(lane % 8, T - 1)];
     float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
     // keys of this wave's tiles (buffered first, then the new ones)
     uint4 kt[NTW][4];
@@ -1439,17 +1468,43 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int x = 0; x < NTW; ++x)
         GcKey[x] = 0.0f;
+    // Drafts form a chain (kvb_verify) or a tree (kvb_verify_tree): the decay of draft i runs
+    // along its own root path, and anc_i has bit j set iff draft j is a strict ancestor of i.
+    // A parent index that does not precede its child is taken as -1 and flagged.
+    int ancRow[4];       // ancestor bits of the draft of accumulator row 4 lq + v
     auto finish_Gc = [&]() {
-        float run = G_prev;
+        float Gi[TMX];   // wave-uniform; constant indices only
+        int anc[TMX];
+        bool bad = false;
+        const bool tree = a.tree != 0;   // uniform; no load sits behind this branch
 #pragma unroll
         for (int i = 0; i < TMX; ++i) {
             const float gi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, g_raw), i));
             bet[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, beta_mine), i));
-            run += i < T ? gi : 0.0f;
-            if (i < 4)
+            float base = i > 0 ? Gi[i > 0 ? i - 1 : 0] : G_prev;   // chain: the previous draft
+            int am = (1 << i) - 1;
+            if (tree) {
+                const int pi = __builtin_amdgcn_readlane(par_raw, i);
+                bad = bad || (i < T && (pi < -1 || pi >= i));
+                base = G_prev;
+                am = 0;
+#pragma unroll
+                for (int j = 0; j < i; ++j) {
+                    const bool is_parent = pi == j;
+                    base = is_parent ? Gi[j] : base;
+                    am = is_parent ? (anc[j] | (1 << j)) : am;
+                }
+            }
+            const float run = base + (i < T ? gi : 0.0f);
+            Gi[i] = run;
+            anc[i] = am;
+            if (i < 4) {
                 GcRow[i] = run;
-            else
+                ancRow[i] = am;
+            } else {
                 GcRow[i - 4] = lq % 2 ? run : GcRow[i - 4];
+                ancRow[i - 4] = lq % 2 ? am : ancRow[i - 4];
+            }
             GcLm = lm % 8 == i ? run : GcLm;
             GcTid = tid == i ? run : GcTid;
 #pragma unroll
@@ -1458,6 +1513,8 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
             if (TAIL && lane == 0)
                 sGc[wave][i] = run;
         }
+        if (bad && tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_BADPATH);
     };
     if constexpr (!EARLY)
         finish_Gc();
@@ -1501,7 +1558,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         state_rows();
         // pins the sums, and whatever derives from the loads younger than the state, to this
         // point: pure arithmetic is otherwise free to drift across the fences
-        asm volatile("" : "+v"(acc0), "+v"(acc1), "+v"(G_prev), "+v"(g_raw), "+v"(beta_mine));
+        asm volatile("" : "+v"(acc0), "+v"(acc1), "+v"(G_prev), "+v"(g_raw), "+v"(beta_mine), "+v"(par_raw));
         __builtin_amdgcn_sched_barrier(0);
         finish_Gc();
         // acc*[v] is row m = 4 lq + v = draft m % 8: apply its gamma
@@ -1529,7 +1586,9 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         for (int v = 0; v < 4; ++v) {
             const int m = 4 * lq + v, i = m % 8;
             const bool isq = m >= 8;
-            const bool ok = i < T && n < nrec && (n < f || (isq ? n - f <= i : n - f < i));
+            // a buffered key is seen by every draft; a new one by its descendants (q rows: and by itself)
+            const bool above = n >= f && ((ancRow[v] >> min(n - f, 31)) & 1);
+            const bool ok = i < T && n < nrec && (n < f || above || (isq && n - f == i));
             const float w = ok ? expf(GcRow[v] - Gkey) : 0.0f;
             o[v] = (isq ? w : -w) * c1[v];
         }
@@ -1655,6 +1714,65 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             *reinterpret_cast<uint4 *>(kw + 32 * st) = wa[st];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// kvb_compact: after kvb_verify_tree, the records of the accepted root path
+// (nodes path[0] < path[1] < ...) move from positions f + path[j] to f + j, so that
+// the accepted drafts are a prefix of the T new records and kvb_flush(accepted)
+// commits them (Sec. 3.3, Eq. 8: the state is updated from the accepted tokens
+// only).  path[j] >= j, so a move never overwrites a record that a later move reads;
+// every thread carries the same element of all records, in order, so no two threads
+// touch the same word.
+// ---------------------------------------------------------------------------
+struct CompactArgs {
+    Store st;
+    const int32_t *slot;
+    const int32_t *path;
+    const int32_t *path_len;
+    int32_t Hk, Hv, cap, T;
+};
+
+template <int D, typename TIn>
+__global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
+{
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x / a.Hv;
+    const int h = blockIdx.x % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    const int f = a.st.fill[s] & FILL_MASK;
+    const int n = a.path_len[b];
+    bool bad = n < 0 || n > a.T || f + a.T > a.cap;
+    int prev = -1;
+    for (int j = 0; j < n && !bad; ++j) {   // uniform
+        const int pj = a.path[(size_t)b * a.T + j];
+        bad = pj <= prev || pj >= a.T;
+        prev = pj;
+    }
+    if (bad) {
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_BADPATH);
+        return;
+    }
+    const size_t unit = (size_t)s * a.Hv + h;
+    float *ub = a.st.buf_u + unit * a.cap * D;
+    float *Gb = a.st.buf_G + unit * a.cap;
+    TIn *kb = static_cast<TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + h / r) * a.cap * D;
+    for (int j = 0; j < n; ++j) {
+        const int src = f + a.path[(size_t)b * a.T + j], dst = f + j;
+        if (src == dst)
+            continue;
+        for (int e = tid; e < D; e += NT)
+            ub[(size_t)dst * D + e] = ub[(size_t)src * D + e];
+        if (h % r == 0)
+            for (int e = tid; e < D; e += NT)
+                kb[(size_t)dst * D + e] = kb[(size_t)src * D + e];
+        if (tid == 0)
+            Gb[dst] = Gb[src];
     }
 }
 
@@ -1832,7 +1950,7 @@ int dispatch(const kvb_shape *sh, F &&f)
 
 int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, int T, const void *q,
                 const void *k, const void *v, const float *g, const float *beta, void *out, void *stream,
-                int advance, int threshold = 0)
+                int advance, int threshold = 0, const int32_t *parent = nullptr)
 {
     int rc = check_common(sh, st, slot);
     if (rc != KVB_OK)
@@ -1845,7 +1963,9 @@ int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, i
     if (sh->B == 0)
         return KVB_OK;
     StepArgs a{dev_store(st), slot, q, k, v, g, beta, static_cast<float *>(out), sh->Hk, sh->Hv, sh->cap, T,
-               sh->scale, advance, threshold, stream_state(sh, st) ? 1 : 0};
+               sh->scale, advance, threshold, stream_state(sh, st) ? 1 : 0,
+               // chain: g stands in as a readable array of at least B*T words whose values are ignored
+               parent ? parent : reinterpret_cast<const int32_t *>(g), parent ? 1 : 0};
     const int blocks = sh->B * sh->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(sh, [&]<int D, typename TIn>() { launch_step<D, TIn>(a, blocks, hs); });
@@ -1879,6 +1999,36 @@ int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                const void *k, const void *v, const float *g, const float *beta, void *out, void *stream)
 {
     return step_common(shape, store, slot, T, q, k, v, g, beta, out, stream, 0);
+}
+
+int kvb_verify_tree(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
+                    const int32_t *parent, const void *q, const void *k, const void *v, const float *g,
+                    const float *beta, void *out, void *stream)
+{
+    if (!parent || !aligned(parent, 4))
+        return KVB_EINVAL;
+    return step_common(shape, store, slot, T, q, k, v, g, beta, out, stream, 0, 0, parent);
+}
+
+int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
+                const int32_t *path, const int32_t *path_len, void *stream)
+{
+    int rc = check_common(shape, store, slot);
+    if (rc != KVB_OK)
+        return rc;
+    if (!path || !path_len || !aligned(path, 4) || !aligned(path_len, 4))
+        return KVB_EINVAL;
+    if (T < 1 || T > KVB_MAX_DRAFTS || T > shape->cap)
+        return KVB_EINVAL;
+    if (shape->B == 0)
+        return KVB_OK;
+    CompactArgs a{dev_store(store), slot, path, path_len, shape->Hk, shape->Hv, shape->cap, T};
+    const int blocks = shape->B * shape->Hv;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    rc = dispatch(shape, [&]<int D, typename TIn>() { launch(kvb_compact_kernel<D, TIn>, blocks, hs, a); });
+    if (rc != KVB_OK)
+        return rc;
+    return finish_launch();
 }
 
 int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, const int32_t *accepted,

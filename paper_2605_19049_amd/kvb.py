@@ -15,9 +15,10 @@ OK, EINVAL, EUNSUPPORTED, EHIP = 0, -1, -2, -3
 F32, BF16 = 0, 1
 MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 64
 STATUS_OVERFLOW = 1
+STATUS_BADPATH = 2
 STORE_STREAM, STORE_RESIDENT = 1, 2
 
-EXPORTS = ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_direct",
+EXPORTS = ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_verify_tree", "kvb_compact", "kvb_direct",
            "kvb_timer_create", "kvb_timer_arm", "kvb_timer_read", "kvb_timer_destroy",
            "kvb_strerror", "kvb_version")
 
@@ -64,8 +65,11 @@ def lib():
         L.kvb_timer_destroy.argtypes = [vp]
         L.kvb_timer_destroy.restype = None
         L.kvb_verify.argtypes = [sp, tp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.kvb_verify_tree.argtypes = [sp, tp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.kvb_compact.argtypes = [sp, tp, vp, i32, vp, vp, vp]
         L.kvb_direct.argtypes = [sp, tp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
-        for name in ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_direct", "kvb_version",
+        for name in ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_verify_tree", "kvb_compact",
+                     "kvb_direct", "kvb_version",
                      "kvb_timer_create", "kvb_timer_arm", "kvb_timer_read"):
             getattr(L, name).restype = ctypes.c_int
         L.kvb_strerror.argtypes = [ctypes.c_int]
@@ -157,6 +161,18 @@ def kvb_verify(sh, st, slot, T, q, k, v, g, beta, out, stream=None, check=True):
     rc = lib().kvb_verify(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), T, _ptr(q), _ptr(k), _ptr(v),
                           _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
     return _check(rc, "kvb_verify", check)
+
+
+def kvb_verify_tree(sh, st, slot, T, parent, q, k, v, g, beta, out, stream=None, check=True):
+    rc = lib().kvb_verify_tree(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), T, _ptr(parent), _ptr(q), _ptr(k),
+                               _ptr(v), _ptr(g), _ptr(beta), _ptr(out), _stream(stream))
+    return _check(rc, "kvb_verify_tree", check)
+
+
+def kvb_compact(sh, st, slot, T, path, path_len, stream=None, check=True):
+    rc = lib().kvb_compact(ctypes.byref(sh), ctypes.byref(st), _ptr(slot), T, _ptr(path), _ptr(path_len),
+                           _stream(stream))
+    return _check(rc, "kvb_compact", check)
 
 
 def kvb_direct(sh, st, slot, lens, Lmax, q, k, v, g, beta, out, stream=None, check=True):

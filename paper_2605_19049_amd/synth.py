@@ -121,3 +121,38 @@ def accepted_lengths(rng, B, T):
 def context_lengths(rng, B, lo, hi):
     """Per-request context length, uniform on lo..hi inclusive."""
     return rng.integers(lo, hi + 1, size=B).astype(np.int32)
+
+
+def draft_trees(rng, B, T, kind="random"):
+    """Parent pointers of B draft trees with T nodes each, parents before children
+    (-1 = the node follows the last committed token).  kind: "random" (parent uniform over
+    -1..i-1), "chain", "star", or "binary" (node i hangs under node (i-1)//2, the root under -1)."""
+    par = np.empty((B, T), np.int32)
+    for i in range(T):
+        if kind == "chain":
+            par[:, i] = i - 1
+        elif kind == "star":
+            par[:, i] = -1
+        elif kind == "binary":
+            par[:, i] = (i - 1) // 2 if i > 0 else -1
+        else:
+            par[:, i] = rng.integers(-1, i, size=B)
+    return par
+
+
+def accepted_paths(rng, parent):
+    """For each tree a random accepted leaf (-1 = nothing accepted, probability 1/(T+1)) and the
+    root path that ends there: (leaf [B], path [B,T] padded with 0, path_len [B])."""
+    B, T = parent.shape
+    leaf = rng.integers(-1, T, size=B).astype(np.int32)
+    path = np.zeros((B, T), np.int32)
+    plen = np.zeros(B, np.int32)
+    for b in range(B):
+        nodes, n = [], int(leaf[b])
+        while n >= 0:
+            nodes.append(n)
+            n = int(parent[b, n])
+        nodes.reverse()
+        plen[b] = len(nodes)
+        path[b, :len(nodes)] = nodes
+    return leaf, path, plen

@@ -86,6 +86,14 @@ class Layer:
         st = self.ds.c(self.with_state if use_state is None else use_state)
         kvb.kvb_verify(self.shape(), st, self.slot, T, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)
 
+    def verify_tree(self, T, parent, tok, out, use_state=None):
+        st = self.ds.c(self.with_state if use_state is None else use_state)
+        kvb.kvb_verify_tree(self.shape(), st, self.slot, T, parent, tok["q"], tok["k"], tok["v"], tok["g"],
+                            tok["beta"], out)
+
+    def compact(self, T, path, path_len):
+        kvb.kvb_compact(self.shape(), self.ds.c(self.with_state), self.slot, T, path, path_len)
+
     def direct(self, lens, Lmax, tok, out):
         kvb.kvb_direct(self.shape(), self.ds.c(False), self.slot, lens, Lmax,
                        tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"], out)

@@ -103,6 +103,22 @@ def test_flush_verify_direct_argument_ranges():
     assert kvb.kvb_direct(sh, st, A, None, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
 
 
+def test_tree_verify_and_compact_argument_ranges():
+    sh = kvb.shape(**GOOD)
+    st = _store()
+    tok = (A, A, A, A, A, A)
+    assert kvb.kvb_verify_tree(sh, st, A, 4, None, *tok, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_verify_tree(sh, st, A, 4, A + 2, *tok, stream=0, check=False) == kvb.EINVAL
+    for T in (0, 9, 17):
+        assert kvb.kvb_verify_tree(sh, st, A, T, A, *tok, stream=0, check=False) == kvb.EINVAL
+        assert kvb.kvb_compact(sh, st, A, T, A, A, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_compact(sh, st, A, 4, None, A, stream=0, check=False) == kvb.EINVAL
+    assert kvb.kvb_compact(sh, st, A, 4, A, None, stream=0, check=False) == kvb.EINVAL
+    empty = kvb.shape(**{**GOOD, "B": 0})
+    assert kvb.kvb_verify_tree(empty, st, A, 4, A, *tok, stream=0, check=False) == kvb.OK
+    assert kvb.kvb_compact(empty, st, A, 4, A, A, stream=0, check=False) == kvb.OK
+
+
 def test_decode_flush_argument_ranges():
     sh = kvb.shape(**GOOD)
     args = (A, A, A, A, A, A, A)

@@ -130,6 +130,111 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     return e_out, e_u, e_S
 
 
+def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=False):
+    """kvb_verify_tree + kvb_compact + kvb_flush against the oracle run along every root path."""
+    rng = np.random.default_rng(seed)
+    fill_hi = min(C - 1, cap - T)
+    S0 = np.zeros((B, Hv, d, d), np.float32) if kv_only else H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
+    fills = synth.buffer_fills(rng, B, 0, fill_hi)
+    wtok = synth.token_stream(rng, B, max(1, fill_hi), Hk, Hv, d, d, in_dtype)
+    vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
+    parent = synth.draft_trees(rng, B, T, kind)
+    leaf, path, plen = synth.accepted_paths(rng, parent)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype)
+    lay.set_state(S0)
+    ragged_warmup(lay, fills, wtok)
+    _, _, S_true, _ = oracle.gdn_sequence(S0, wtok["q"], wtok["k"], wtok["v"], wtok["g"], wtok["beta"], lens=fills)
+    o_ref, u_ref, S_acc = oracle.kvb_verify_tree_expected(S_true, vtok["q"], vtok["k"], vtok["v"], vtok["g"],
+                                                          vtok["beta"], parent, accepted_leaf=leaf)
+    state_before = lay.ds.state.clone()
+    out = torch.full((B, T, Hv, d), float("nan"), dtype=torch.float32, device="cuda")
+    lay.verify_tree(T, H.dev(parent), H.upload_tokens(vtok, in_dtype), out, use_state=not kv_only)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.ds.state, state_before), "kvb_verify_tree wrote the state"
+    assert np.array_equal(lay.fill(), fills), "kvb_verify_tree changed fill"
+    e_out = H.rel_err(out.cpu().numpy(), o_ref)
+    u_got = np.stack([lay.ds.buf_u[b, :, fills[b]:fills[b] + T].cpu().numpy() for b in range(B)])
+    e_u = H.rel_err(u_got.transpose(0, 2, 1, 3), u_ref)
+    # accepted root path to the front, commit it, fold everything
+    lay.compact(T, H.dev(path), H.dev(plen))
+    lay.flush(C, accepted=H.dev(plen))
+    torch.cuda.synchronize()
+    m = fills + plen
+    assert np.array_equal(lay.fill(), np.where(m >= C, 0, m))
+    lay.flush(1)
+    torch.cuda.synchronize()
+    e_S = H.rel_err(lay.get_state(), S_acc)
+    assert not lay.status().any()
+    return e_out, e_u, e_S
+
+
+@pytest.mark.parametrize("T, kind", [(2, "random"), (4, "random"), (5, "random"), (8, "random"), (8, "binary"),
+                                     (6, "star"), (7, "chain")])
+def test_verify_tree_small(T, kind):
+    e = _tree_case(B=6, Hk=2, Hv=4, d=128, C=16, cap=16 + T - 1, T=T, in_dtype="bf16", seed=130 + T, kind=kind)
+    say("verify_tree T=%d %s rel err out/u/state-after-commit: %.2e %.2e %.2e" % ((T, kind) + e))
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_verify_tree_fp32_d64_long_buffer_and_kv_only():
+    """The vector-ALU kernel (fp32 inputs, d != 128), the 64-record window, and no state at all."""
+    e = _tree_case(B=3, Hk=1, Hv=2, d=32, C=8, cap=12, T=4, in_dtype="f32", seed=141)
+    assert max(e) < H.TOL["f32"], e
+    e = _tree_case(B=3, Hk=2, Hv=2, d=64, C=8, cap=16, T=8, in_dtype="bf16", seed=142)
+    assert max(e) < H.TOL["bf16"], e
+    e = _tree_case(B=3, Hk=2, Hv=4, d=128, C=64, cap=72, T=8, in_dtype="bf16", seed=143)
+    assert max(e) < H.TOL["bf16"], e
+    e = _tree_case(B=4, Hk=2, Hv=4, d=128, C=16, cap=20, T=4, in_dtype="bf16", seed=144, kv_only=True)
+    assert max(e) < H.TOL["bf16"], e
+
+
+def test_verify_tree_chain_is_kvb_verify_bit_for_bit():
+    """parent[i] = i - 1 must give exactly what kvb_verify gives (same kernel, same arithmetic)."""
+    rng = np.random.default_rng(150)
+    B, Hk, Hv, d, T, cap = 5, 2, 4, 128, 4, 20
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, "bf16", 8)
+    fills = synth.buffer_fills(rng, B, 0, 15)
+    wtok = synth.token_stream(rng, B, 15, Hk, Hv, d, d, "bf16")
+    vtok = H.upload_tokens(synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16"), "bf16")
+    outs = []
+    for tree in (False, True):
+        lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype="bf16")
+        lay.set_state(S0)
+        ragged_warmup(lay, fills, wtok)
+        out = torch.empty((B, T, Hv, d), dtype=torch.float32, device="cuda")
+        if tree:
+            lay.verify_tree(T, H.dev(synth.draft_trees(rng, B, T, "chain")), vtok, out)
+        else:
+            lay.verify(T, vtok, out)
+        torch.cuda.synchronize()
+        outs.append((out.cpu().numpy(), lay.ds.buf_u.cpu().numpy(), lay.ds.buf_G.cpu().numpy()))
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
+
+
+def test_bad_trees_and_paths_are_flagged_not_followed():
+    rng = np.random.default_rng(151)
+    B, Hk, Hv, d, T, cap = 3, 1, 2, 128, 4, 8
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype="bf16")
+    lay.set_state(np.zeros((B, Hv, d, d), np.float32))
+    vtok = H.upload_tokens(synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16"), "bf16")
+    parent = np.array([[-1, 0, 1, 2], [-1, 1, 0, 0], [-1, 0, 0, -7]], np.int32)   # rows 1, 2: not well formed
+    out = torch.empty((B, T, Hv, d), dtype=torch.float32, device="cuda")
+    lay.verify_tree(T, H.dev(parent), vtok, out)
+    torch.cuda.synchronize()
+    assert list(lay.status()) == [0, kvb.STATUS_BADPATH, kvb.STATUS_BADPATH]
+    assert torch.isfinite(out).all()
+    lay.ds.status.zero_()
+    u_before = lay.ds.buf_u.clone()
+    path = np.array([[0, 1, 3, 0], [2, 1, 0, 0], [0, 5, 0, 0]], np.int32)
+    plen = np.array([3, 2, 2], np.int32)    # row 0 fine; row 1 decreasing; row 2 out of range
+    lay.compact(T, H.dev(path), H.dev(plen))
+    torch.cuda.synchronize()
+    assert list(lay.status()) == [0, kvb.STATUS_BADPATH, kvb.STATUS_BADPATH]
+    assert torch.equal(lay.ds.buf_u[1:], u_before[1:])
+    assert torch.equal(lay.ds.buf_u[0, :, 2], u_before[0, :, 3])
+
+
 @pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 8])
 def test_verify_small(T):
     e = _verify_case(B=6, Hk=2, Hv=4, d=128, C=16, cap=16 + T - 1, T=T, in_dtype="bf16", seed=30 + T)
@@ -156,6 +261,15 @@ def test_spec_verify_full():
     w = synth.WORKLOADS["spec_verify"]
     e = _verify_case(w.B, w.Hk, w.Hv, w.dk, w.C, w.cap, w.T, w.in_dtype, w.seed)
     say("spec_verify rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+
+
+def test_spec_verify_tree_full():
+    """Workload 3's size with tree-shaped drafts: B=128, fill ~U(0,15), a random 8-node tree per
+    request, a random accepted root path; every draft checked along its own path."""
+    w = synth.WORKLOADS["spec_verify"]
+    e = _tree_case(w.B, w.Hk, w.Hv, w.dk, w.C, 24, 8, w.in_dtype, w.seed + 1)
+    say("spec_verify (trees of 8) rel err out/u/state: %.2e %.2e %.2e" % e)
     assert max(e) < H.TOL["bf16"]
 
 
