@@ -36,6 +36,9 @@ def parse():
                     help="override the chunk size C (and cap); 1 = the fused recurrent step, for the Fig. 3 style sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--block-size", type=int, default=0,
+                    help="paged record buffers: blocks of this many records dealt at random from a shared pool "
+                         "(0 = the contiguous layout; bytes per step are the same)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-paths", action="store_true")
     return ap.parse_args()
@@ -45,14 +48,20 @@ class DecodeJob:
     """Device-resident workload: one store holding every layer's slots, a ring of token
     inputs, pre-marshalled calls (one per layer and ring entry)."""
 
-    def __init__(self, w, ring=32, fused=True):
+    def __init__(self, w, ring=32, fused=True, block_size=0):
         import numpy as np
         import torch
         from paper_2605_19049_amd import kvb, synth
         self.w, self.torch, self.kvb, self.np = w, torch, kvb, np
         dt = kvb.BF16 if w.in_dtype == "bf16" else kvb.F32
         self.L = w.layers
-        self.ds = kvb.DeviceStore(w.B * self.L, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt)
+        if block_size:
+            mb = -(-w.cap // block_size)
+            table = np.random.default_rng(w.seed + 7).permutation(w.B * self.L * mb).reshape(w.B * self.L, mb)
+            self.ds = kvb.DeviceStore(w.B * self.L, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt, block_size=block_size,
+                                      block_table=table)
+        else:
+            self.ds = kvb.DeviceStore(w.B * self.L, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt)
         self.sh = kvb.shape(w.B, w.Hk, w.Hv, w.dk, w.dv, w.cap, dt, 1.0)
         # many layers: each state is next read a whole model pass later -> stream it
         self.st = self.ds.c(flags=kvb.STORE_STREAM if self.L > 1 else 0)
@@ -266,7 +275,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     fused = args.step == "fused"
-    job = DecodeJob(w, fused=fused)
+    job = DecodeJob(w, fused=fused, block_size=args.block_size)
     L = job.L
     # untimed: build a real committed state by decoding a prompt-sized prefix, then W warm-up steps
     job.run(w.prefix + W)
@@ -337,7 +346,8 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hk": w.Hk, "Hv": w.Hv, "dk": w.dk, "dv": w.dv,
                    "C": w.C, "cap": w.cap, "layers": L, "in_dtype": w.in_dtype, "state_dtype": "f32",
                    "step": step_desc + (" through each of %d layers" % L if L > 1 else ""), "launch": args.mode,
-                   "state_MiB": L * units * w.dk * w.dv * 4 / 2 ** 20},
+                   "state_MiB": L * units * w.dk * w.dv * 4 / 2 ** 20,
+                   "records": ("blocks of %d from a shuffled pool" % args.block_size) if args.block_size else "contiguous"},
         "full_cycle": {"algorithmic_bytes_per_layer_step": cycle_bytes,
                        "algorithmic_GBps": cycle_bytes / per_layer_step / 1e9,
                        "frac_of_hbm_peak": cycle_bytes / per_layer_step / 1e9 / HBM_PEAK_GBS,

@@ -49,6 +49,7 @@ extern "C" {
 #define KVB_MAX_CAP        128 /* largest `cap` (the paper buffers at most d records, Sec. 3.4) */
 #define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
 #define KVB_MAX_DIRECT_LEN  64 /* largest Lmax of kvb_direct in this build                      */
+#define KVB_MAX_BLOCKS      16 /* longest block-table row (KVB_MAX_CAP / smallest block)        */
 
 /* kvb_store.flags: how the state should travel through the caches.  With neither bit the
  * library streams (non-temporal loads) when one call touches more state than the 256 MB
@@ -88,6 +89,20 @@ typedef struct kvb_store {
     int32_t  n_slots; /* slots in the arrays above; requests whose slot is outside
                          0..n_slots-1 are skipped                                           */
     int32_t  flags;   /* KVB_STORE_* hints, 0 = let the library decide                      */
+    /* Paged record buffers (Sec. 3.1: a request's buffer is made of blocks of 8 or 16 records
+     * drawn from a pool shared by all requests).  block_table == NULL (and the three sizes 0):
+     * the layout above, one block of cap records per slot.  Otherwise record l of slot s lives
+     * in block block_table[s][l / block_size] at position l % block_size, and the record
+     * arrays are pools of n_blocks blocks:
+     *   buf_k [n_blocks, Hk, block_size, dk]   buf_u [n_blocks, Hv, block_size, dv]
+     *   buf_G [n_blocks, Hv, block_size]
+     * state, fill and status stay per slot.  Only the entries that cover records 0..cap-1 are
+     * read; ids outside 0..n_blocks-1 are clamped into the pool.  Two requests of one call must
+     * not share a block.                                                                     */
+    const int32_t *block_table; /* device [n_slots, max_blocks] or NULL                       */
+    int32_t  block_size;        /* 8, 16, 32, 64 or 128 records                               */
+    int32_t  max_blocks;        /* 1..KVB_MAX_BLOCKS, block_size * max_blocks >= cap          */
+    int32_t  n_blocks;          /* blocks in the pools                                        */
 } kvb_store;
 
 /*

@@ -169,7 +169,69 @@ struct Store {
     int32_t *fill;
     int32_t *status;
     int32_t n_slots;
+    // Paged record buffers (Sec. 3.1: blocks of 8 or 16 records from a pool shared by all requests).
+    // block_table == nullptr: slot s owns the records s*cap .. s*cap+cap-1 of each head, as one block.
+    const int32_t *block_table;   // [n_slots, max_blocks] block ids
+    int32_t block_size;           // records per block, a power of two (cap when not paged)
+    int32_t max_blocks;           // row length of block_table (1 when not paged)
+    int32_t n_blocks;             // blocks in the pools; ids are clamped into 0..n_blocks-1
 };
+
+// Where record l of the request lives.  The record arrays are [blocks, heads, block_size, ...]:
+// a head's records inside a block are contiguous.  Without a block table the block is the slot
+// and block_size is cap, which is the contiguous layout.  Each wave keeps its own copy of the
+// request's block-table row in LDS (written and read by the same wave, so no barrier), filled
+// from one small vector load that is issued before the state loads and therefore never waits
+// for them.
+constexpr int MAX_BLOCKS = KVB_MAX_BLOCKS;   // cap <= 128, block_size >= 8
+// PAGED is a compile-time switch of every kernel: the contiguous layout then costs nothing
+// (measured: a run-time flag cost the decode step 2 %; and a dummy load from fill[s] in its
+// place doubled the step time, every wave's first load queueing behind the ticket atomics
+// that the other heads of the request issue on that word).
+template <bool PAGED>
+struct Pages {
+    const int *tab;   // this wave's LDS copy of the row
+    int s, bs, lg;
+    __device__ __forceinline__ int blk(int l) const
+    {
+        if constexpr (PAGED)
+            return tab[l >> lg];
+        else
+            return s;
+    }
+    __device__ __forceinline__ int off(int l) const { return PAGED ? (l & (bs - 1)) : l; }
+    // row of record l of head `head` (H heads per block) in units of one record
+    __device__ __forceinline__ size_t row(int l, int H, int head) const
+    {
+        return ((size_t)blk(l) * H + head) * bs + off(l);
+    }
+};
+// The lane's entry of the block-table row (lanes >= max_blocks repeat the last entry).
+template <bool PAGED>
+__device__ __forceinline__ int load_block_id(const Store &st, int s, int lane)
+{
+    if constexpr (PAGED)
+        return st.block_table[(size_t)s * st.max_blocks + min(lane, st.max_blocks - 1)];
+    else
+        return 0;
+}
+template <bool PAGED>
+__device__ __forceinline__ Pages<PAGED> make_pages(const Store &st, int s, int cap, int *tab, int lane, int id)
+{
+    Pages<PAGED> pg;
+    pg.tab = tab;
+    pg.s = s;
+    if constexpr (PAGED) {
+        if (lane < MAX_BLOCKS)
+            tab[lane] = min(max(id, 0), st.n_blocks - 1);
+        pg.bs = st.block_size;
+        pg.lg = 31 - __builtin_clz(st.block_size);
+    } else {
+        pg.bs = cap;
+        pg.lg = 0;
+    }
+    return pg;
+}
 
 struct StepArgs {
     Store st;
@@ -218,7 +280,7 @@ __device__ __forceinline__ float group_sum(float x)
 // workgroup applies the deferred update S <- gamma_f S0 + sum_{l<=f} Gamma_fl k_l^T u_l to
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
-template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM>
+template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
 {
     constexpr int LPR = D / 4;       // lanes covering one state row with float4
@@ -246,6 +308,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     __shared__ float cQ[TM][NC];     // Gamma_il (q_i.k_l), 0 for l >  f+i
     __shared__ __attribute__((aligned(16))) float red[NW][TM][2][D];
     __shared__ __attribute__((aligned(16))) float kh[FUSE ? LT : 1][D];  // Gamma_fl k_l tile
+    __shared__ int sBlk[NW][MAX_BLOCKS];
     __shared__ __attribute__((aligned(16))) float uu[FUSE ? LT : 1][D];  // u_l tile
 
     const int tid = threadIdx.x;
@@ -267,9 +330,10 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     const TIn *qin = static_cast<const TIn *>(a.q);
     const TIn *kin = static_cast<const TIn *>(a.k);
     const TIn *vin = static_cast<const TIn *>(a.v);
-    const float *Gbuf = a.st.buf_G + unit * cap;
-    const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
-    const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u + unit * cap * D);
+    const float *Gbuf = a.st.buf_G;                              // record l of this head: Gbuf[ru(l)]
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k);        //                        kb + rk(l) * D
+    const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u);   //                  up + ru(l) * LPR
+    const int blk_id = load_block_id<PAGED>(a.st, s, tid % 64);
 
     // ---- 1. loads that need only the request index --------------------------
     // All vector loads of this kernel are issued as raw bits from always-valid addresses (an
@@ -333,13 +397,16 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         }
         return;
     }
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, cap, sBlk[tid / 64], tid % 64, blk_id);
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };    // row of record l in buf_u / buf_G
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };   // row of record l in buf_k
     // cumulative log decay of the new rows (uniform)
     // Gc[i]: cumulative log decay of new row i along its own root path (a chain unless the
     // drafts form a tree); anc[i]: bit j set iff new row j is a strict ancestor of row i.
     // A parent index that does not precede its child is taken as -1 and flagged.
     float Gc[TM];
     int anc[TM];
-    float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
+    float G_prev = f > 0 ? Gbuf[ru(f - 1)] : 0.0f;
     auto finish_Gc = [&]() {
         bool bad = false;
 #pragma unroll
@@ -368,14 +435,14 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     for (int p = 0; p < KP; ++p) {
         const int l = grp + NG * p;
         const int lc = l < f ? l : 0;
-        kl_raw[p] = load_raw8(kb + (size_t)lc * D + 8 * sub);
-        Gl[p] = Gbuf[lc];
+        kl_raw[p] = load_raw8(kb + rk(lc) * D + 8 * sub);
+        Gl[p] = Gbuf[ru(lc)];
     }
     float4 ur[UP];
 #pragma unroll
     for (int j = 0; j < UP; ++j) {
         const int l = rg + RPP * j;
-        ur[j] = up[(size_t)(l < f ? l : 0) * LPR + c4];
+        ur[j] = up[ru(l < f ? l : 0) * LPR + c4];
     }
     if constexpr (HAS_STATE && !EARLY)
         issue_state();
@@ -457,7 +524,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         }
         for (int l = KP * NG + grp; TAIL && l < f; l += NG) {   // records beyond the register window
             float kx[8];
-            load8(kb + (size_t)l * D + 8 * sub, kx);
+            load8(kb + rk(l) * D + 8 * sub, kx);
             float dkk = 0.0f, dq = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -467,7 +534,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             dkk = group_sum<GL>(dkk);
             dq = group_sum<GL>(dq);
             if (sub == 0) {
-                const float w = expf(Gc[0] - Gbuf[l]);
+                const float w = expf(Gc[0] - Gbuf[ru(l)]);
                 cK[0][l] = w * dkk;
                 cQ[0][l] = w * dq;
             }
@@ -520,8 +587,8 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             float kx[8];
             float Gx = 0.0f;
             if (l < f) {
-                load8(kb + (size_t)l * D + 8 * sub, kx);
-                Gx = Gbuf[l];
+                load8(kb + rk(l) * D + 8 * sub, kx);
+                Gx = Gbuf[ru(l)];
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -573,7 +640,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         }
     }
     for (int l = UP * RPP + rg; TAIL && l < f; l += RPP) {
-        const float4 u = up[(size_t)l * LPR + c4];
+        const float4 u = up[ru(l) * LPR + c4];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (i < T) {
@@ -655,7 +722,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                 uprev[i] = ui;
                 u_new = ui;
                 a.out[row * D + tid] = a.scale * ao;
-                a.st.buf_u[(unit * cap + f + i) * D + tid] = ui;
+                a.st.buf_u[ru(f + i) * D + tid] = ui;
             }
         }
     }
@@ -665,11 +732,11 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
         for (int j = 0; j < TM; ++j)
             if (j == tid)
                 gv = Gc[j];
-        a.st.buf_G[unit * cap + f + tid] = gv;
+        a.st.buf_G[ru(f + tid)] = gv;
     }
     if (h % r == 0 && tid < T * (D / 8)) {   // the threads that loaded the new k rows store them
-        TIn *kw = static_cast<TIn *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f) * D;
-        store_raw8(kw + (size_t)nr_i * D + 8 * nr_e, k_raw);
+        TIn *kw = static_cast<TIn *>(a.st.buf_k) + rk(f + nr_i) * D;
+        store_raw8(kw + 8 * nr_e, k_raw);
     }
     int new_fill = f + T;
     if constexpr (FUSE) {
@@ -680,7 +747,7 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
             for (int p = 0; p < NPASS; ++p) {
                 sreg[p].x *= gam; sreg[p].y *= gam; sreg[p].z *= gam; sreg[p].w *= gam;
             }
-            const float *ub = a.st.buf_u + unit * cap * D;
+            const float *ub = a.st.buf_u;
             // one LDS tile of LT records: record f itself comes from this workgroup's registers
             auto inject_new = [&](int l0) {
                 if (f >= l0 && f < l0 + LT) {
@@ -742,8 +809,8 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
                 for (int x = 0; x < EPT; ++x) {
                     const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
                     if (l < f) {
-                        kh[idx / D][e] = expf(Gc[0] - Gbuf[l]) * to_f32(kb[(size_t)l * D + e]);
-                        uu[idx / D][e] = ub[(size_t)l * D + e];
+                        kh[idx / D][e] = expf(Gc[0] - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
+                        uu[idx / D][e] = ub[ru(l) * D + e];
                     } else if (l > f) {
                         kh[idx / D][e] = 0.0f;
                         uu[idx / D][e] = 0.0f;
@@ -776,7 +843,7 @@ struct FlushArgs {
     int32_t Hk, Hv, cap, threshold;
 };
 
-template <int D, typename TIn>
+template <int D, typename TIn, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 {
     constexpr int LPR = D / 4;
@@ -787,6 +854,7 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 
     __shared__ __attribute__((aligned(16))) float kh[LT][D];  // Gamma_{m-1,l} k_l
     __shared__ __attribute__((aligned(16))) float uu[LT][D];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
 
     const int tid = threadIdx.x;
     const int lb = logical_block();
@@ -819,10 +887,13 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
         ticket = take_ticket(&a.st.fill[s]);
     const int rg = tid / LPR, c4 = tid % LPR;
     const size_t unit = (size_t)s * a.Hv + h;
-    const float *Gbuf = a.st.buf_G + unit * cap;
-    const TIn *kb = static_cast<const TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
-    const float *ub = a.st.buf_u + unit * cap * D;
-    const float Glast = Gbuf[m - 1];
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, cap, sBlk[tid / 64], tid % 64, load_block_id<PAGED>(a.st, s, tid % 64));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
+    const float *Gbuf = a.st.buf_G;
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k);
+    const float *ub = a.st.buf_u;
+    const float Glast = Gbuf[ru(m - 1)];
 
     // first record tile, then the state tile, so the tile's loads retire first
     float kt[EPT], ut[EPT];
@@ -831,8 +902,8 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
         for (int x = 0; x < EPT; ++x) {
             const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
             if (l < m) {
-                kt[x] = expf(Glast - Gbuf[l]) * to_f32(kb[(size_t)l * D + e]);
-                ut[x] = ub[(size_t)l * D + e];
+                kt[x] = expf(Glast - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
+                ut[x] = ub[ru(l) * D + e];
             } else {
                 kt[x] = 0.0f;
                 ut[x] = 0.0f;
@@ -898,7 +969,7 @@ struct DirectArgs {
     float scale;
 };
 
-template <int D, typename TIn>
+template <int D, typename TIn, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 {
     constexpr int LM = KVB_MAX_DIRECT_LEN;
@@ -909,6 +980,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
     __shared__ float sU[LM][D];
     __shared__ float sG[LM];
     __shared__ float sB[LM];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
 
     const int tid = threadIdx.x;
     const int lb = logical_block();
@@ -927,7 +999,9 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
         if (tid == 0 && a.st.status)
             atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
     }
-    const size_t unit = (size_t)s * a.Hv + h;
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[tid / 64], tid % 64, load_block_id<PAGED>(a.st, s, tid % 64));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
     const TIn *qin = static_cast<const TIn *>(a.q);
     const TIn *kin = static_cast<const TIn *>(a.k);
     const TIn *vin = static_cast<const TIn *>(a.v);
@@ -978,16 +1052,16 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
             sU[i][tid] = ui;
             o = fmaf(cQ[i][i], ui, o);
             a.out[row * D + tid] = a.scale * o;
-            a.st.buf_u[(unit * a.cap + i) * D + tid] = ui;
+            a.st.buf_u[ru(i) * D + tid] = ui;
         }
     }
     if (tid < L)
-        a.st.buf_G[unit * a.cap + tid] = sG[tid];
+        a.st.buf_G[ru(tid)] = sG[tid];
     if (h % r == 0) {
-        TIn *kb = static_cast<TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * a.cap * D;
+        TIn *kb = static_cast<TIn *>(a.st.buf_k);
         for (int idx = tid; idx < L * D; idx += NT) {
             const int i = idx / D, e = idx % D;
-            kb[(size_t)i * D + e] = kin[(((size_t)b * Lmax + i) * a.Hk + hk) * D + e];
+            kb[rk(i) * D + e] = kin[(((size_t)b * Lmax + i) * a.Hk + hk) * D + e];
         }
     }
     if (h == 0 && tid == 0)
@@ -1057,6 +1131,7 @@ __device__ __forceinline__ f32x4_t gram16(const bf16_t *arow, const bf16_t *brow
     return c;
 }
 
+template <bool PAGED>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void kvb_direct_mfma_kernel(
     const DirectArgs a)
 {
@@ -1075,6 +1150,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
     __shared__ float sG[LM];
     __shared__ float sB[LM];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
     bf16_t *sK = reinterpret_cast<bf16_t *>(region);
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NLOW;
@@ -1103,7 +1179,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
             a.st.fill[s] = 0;
         return;
     }
-    const size_t unit = (size_t)s * a.Hv + h;
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
     const bf16_t *qin = static_cast<const bf16_t *>(a.q);
     const bf16_t *kin = static_cast<const bf16_t *>(a.k);
     const bf16_t *vin = static_cast<const bf16_t *>(a.v);
@@ -1162,16 +1240,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
         sG[lane] = gv;
         sB[lane] = bv;
         if (lane < L)
-            a.st.buf_G[unit * a.cap + lane] = gv;
+            a.st.buf_G[ru(lane)] = gv;
     }
     // stage K, Q; the thread that loaded a piece of K also appends it to the buffer
-    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * a.cap * D;
+    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k);
 #pragma unroll
     for (int p = 0; p < NB; ++p) {
         if (p < nb) {   // uniform
             *reinterpret_cast<u32x4_t *>(sK + (16 * p + srow) * GS + 8 * sc8) = kst[p];
             if (h % r == 0 && 16 * p + srow < L)
-                *reinterpret_cast<u32x4_t *>(kb + (size_t)(16 * p + srow) * D + 8 * sc8) = kst[p];
+                *reinterpret_cast<u32x4_t *>(kb + rk(16 * p + srow) * D + 8 * sc8) = kst[p];
         }
     }
     __syncthreads();
@@ -1272,7 +1350,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     // tiles are adjacent columns, so v arrives as one 4-byte load and results leave as float2
     f32x4_t U[NB][2];
     float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
-    float *up = a.st.buf_u + unit * a.cap * D;
+    float *up = a.st.buf_u;
 #pragma unroll
     for (int d = 0; d < NB; ++d) {
         if (d < nb) {   // uniform
@@ -1311,7 +1389,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
                 if (i < L) {
                     *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
                         make_float2(a.scale * o[0][v], a.scale * o[1][v]);
-                    *reinterpret_cast<float2 *>(up + ((uint32_t)i * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                    *reinterpret_cast<float2 *>(up + (ru(i) * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
                 }
             }
         }
@@ -1335,7 +1413,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 // one 128-byte line per row).  MFMA layouts: see kvb_direct_mfma_kernel; for 16x16x4 fp32
 // lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives C[4*(l/16)+v][l%16].
 // ---------------------------------------------------------------------------
-template <int WREC, bool HAS_STATE, bool STREAM>
+template <int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 {
     constexpr int D = 128;
@@ -1350,6 +1428,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     __shared__ __attribute__((aligned(16))) float sW[D][16];
     __shared__ __attribute__((aligned(16))) float cW[NTILE * 16][16];
     __shared__ __attribute__((aligned(16))) float fin[16][D];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
     __shared__ float sGc[TAIL ? NW : 1][TMX];   // per-wave table for the keys beyond the register window
 
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
@@ -1368,9 +1447,10 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     const bf16_t *qin = static_cast<const bf16_t *>(a.q);
     const bf16_t *kin = static_cast<const bf16_t *>(a.k);
     const bf16_t *vin = static_cast<const bf16_t *>(a.v);
-    const float *Gbuf = a.st.buf_G + unit * cap;
-    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k) + ((size_t)s * a.Hk + hk) * cap * D;
-    const float *ub = a.st.buf_u + unit * cap * D;
+    const float *Gbuf = a.st.buf_G;                               // record l of this head: Gbuf[ru(l)]
+    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k);   //                        kb + rk(l) * D
+    const float *ub = a.st.buf_u;                                 //                        ub + ru(l) * D
+    const int blk_id = load_block_id<PAGED>(a.st, s, lane);
 
     const int lm = lane % 16, lq = lane / 16;   // MFMA row/column index and k index of this lane
     const int col2 = 32 * wave + 2 * lm;
@@ -1415,6 +1495,9 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         return;
     }
     const int nrec = f + T;
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, cap, sBlk[wave], lane, blk_id);
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
     const int ntile = (nrec + 15) / 16;
 
     // ---- 3. loads that need the fill ------------------------------------------
@@ -1424,16 +1507,16 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     float g_raw = a.g[go];
     float beta_mine = a.beta[go];
     int par_raw = a.parent[(size_t)b * T + min(lane % 8, T - 1)];
-    float G_prev = f > 0 ? Gbuf[f - 1] : 0.0f;
+    float G_prev = f > 0 ? Gbuf[ru(f - 1)] : 0.0f;
     // keys of this wave's tiles (buffered first, then the new ones)
     uint4 kt[NTW][4];
     float Gn[NTW];
 #pragma unroll
     for (int x = 0; x < NTW; ++x) {
         const int n = 16 * (wave + NW * x) + lm;
-        const bf16_t *kp = n < f ? kb + (size_t)n * D
+        const bf16_t *kp = n < f ? kb + rk(n) * D
                                  : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
-        Gn[x] = Gbuf[n < f ? n : 0];
+        Gn[x] = Gbuf[ru(n < f ? n : 0)];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             kt[x][st] = *reinterpret_cast<const uint4 *>(kp + 8 * lq + 32 * st);
@@ -1444,7 +1527,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int sq = 0; sq < WQ; ++sq) {
         const int l = 4 * sq + lq;
-        uq[sq] = *reinterpret_cast<const float2 *>(ub + (size_t)(l < f ? l : 0) * D + col2);
+        uq[sq] = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
     }
     // v of this wave's columns (used by lanes 0..31 in the last stage)
     const int colf = 32 * wave + lane % 32;
@@ -1602,13 +1685,13 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     }
     for (int tile = wave + NW * NTW; TAIL && tile < ntile; tile += NW) {   // keys beyond the register window
         const int n = 16 * tile + lm;
-        const bf16_t *kp = n < f ? kb + (size_t)n * D
+        const bf16_t *kp = n < f ? kb + rk(min(n, cap - 1)) * D
                                  : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
         uint4 kk[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             kk[st] = *reinterpret_cast<const uint4 *>(kp + 8 * lq + 32 * st);
-        const float Gb = Gbuf[n < f ? n : 0];
+        const float Gb = Gbuf[ru(n < f ? n : 0)];
         key_tile(tile, kk, n < f ? Gb : sGc[wave][min(max(n - f, 0), TMX - 1)]);
     }
     __syncthreads();
@@ -1626,7 +1709,7 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     }
     for (int sq = WQ; TAIL && sq < nquad; ++sq) {
         const int l = 4 * sq + lq;
-        const float2 u = *reinterpret_cast<const float2 *>(ub + (size_t)(l < f ? l : 0) * D + col2);
+        const float2 u = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
         const float aw = cW[l][lm];
         acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.x : 0.0f, acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.y : 0.0f, acc1, 0, 0, 0);
@@ -1704,13 +1787,13 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
         const bool is_u = rr < T;
         const int i = is_u ? rr : rr - T;
         const float4 val = *reinterpret_cast<const float4 *>(&fin[is_u ? i : 8 + i][4 * c4]);
-        float *dst = is_u ? a.st.buf_u + (unit * cap + f + i) * D : a.out + (((size_t)b * T + i) * a.Hv + h) * D;
+        float *dst = is_u ? a.st.buf_u + ru(f + i) * D : a.out + (((size_t)b * T + i) * a.Hv + h) * D;
         *reinterpret_cast<float4 *>(dst + 4 * c4) = val;
     }
     if (tid < T)
-        a.st.buf_G[unit * cap + f + tid] = GcTid;
+        a.st.buf_G[ru(f + tid)] = GcTid;
     if (h % r == 0 && wave == 0 && lm < T) {   // lanes holding k rows store them
-        bf16_t *kw = static_cast<bf16_t *>(a.st.buf_k) + (((size_t)s * a.Hk + hk) * cap + f + lm) * D + 8 * lq;
+        bf16_t *kw = static_cast<bf16_t *>(a.st.buf_k) + rk(f + lm) * D + 8 * lq;
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             *reinterpret_cast<uint4 *>(kw + 32 * st) = wa[st];
@@ -1734,9 +1817,10 @@ struct CompactArgs {
     int32_t Hk, Hv, cap, T;
 };
 
-template <int D, typename TIn>
+template <int D, typename TIn, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
 {
+    __shared__ int sBlk[NW][MAX_BLOCKS];
     const int tid = threadIdx.x;
     const int b = blockIdx.x / a.Hv;
     const int h = blockIdx.x % a.Hv;
@@ -1758,21 +1842,23 @@ __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
             atomicOr(&a.st.status[s], KVB_STATUS_BADPATH);
         return;
     }
-    const size_t unit = (size_t)s * a.Hv + h;
-    float *ub = a.st.buf_u + unit * a.cap * D;
-    float *Gb = a.st.buf_G + unit * a.cap;
-    TIn *kb = static_cast<TIn *>(a.st.buf_k) + ((size_t)s * a.Hk + h / r) * a.cap * D;
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[tid / 64], tid % 64, load_block_id<PAGED>(a.st, s, tid % 64));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, h / r); };
+    float *ub = a.st.buf_u;
+    float *Gb = a.st.buf_G;
+    TIn *kb = static_cast<TIn *>(a.st.buf_k);
     for (int j = 0; j < n; ++j) {
         const int src = f + a.path[(size_t)b * a.T + j], dst = f + j;
         if (src == dst)
             continue;
         for (int e = tid; e < D; e += NT)
-            ub[(size_t)dst * D + e] = ub[(size_t)src * D + e];
+            ub[ru(dst) * D + e] = ub[ru(src) * D + e];
         if (h % r == 0)
             for (int e = tid; e < D; e += NT)
-                kb[(size_t)dst * D + e] = kb[(size_t)src * D + e];
+                kb[rk(dst) * D + e] = kb[rk(src) * D + e];
         if (tid == 0)
-            Gb[dst] = Gb[src];
+            Gb[ru(dst)] = Gb[ru(src)];
     }
 }
 
@@ -1796,6 +1882,15 @@ int check_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot)
         return KVB_EINVAL;
     if (st->n_slots <= 0 || !st->buf_k || !st->buf_u || !st->buf_G || !st->fill)
         return KVB_EINVAL;
+    if (st->block_table) {   // paged record buffers
+        const int bs = st->block_size;
+        if (bs < 8 || bs > KVB_MAX_CAP || (bs & (bs - 1)) != 0)
+            return KVB_EINVAL;
+        if (st->max_blocks < 1 || st->max_blocks > KVB_MAX_BLOCKS || st->n_blocks < 1)
+            return KVB_EINVAL;
+        if ((long long)bs * st->max_blocks < sh->cap || !aligned(st->block_table, 4))
+            return KVB_EINVAL;
+    }
     if (!aligned(st->state, 16) || !aligned(st->buf_k, 16) || !aligned(st->buf_u, 16) ||
         !aligned(st->buf_G, 4) || !aligned(st->fill, 4) || !aligned(st->status, 4) || !aligned(slot, 4))
         return KVB_EINVAL;
@@ -1834,7 +1929,9 @@ bool stream_state(const kvb_shape *sh, const kvb_store *st)
 
 Store dev_store(const kvb_store *st)
 {
-    return Store{st->state, st->buf_k, st->buf_u, st->buf_G, st->fill, st->status, st->n_slots};
+    return Store{st->state, st->buf_k, st->buf_u, st->buf_G, st->fill, st->status, st->n_slots,
+                 st->block_table, st->block_table ? st->block_size : 0, st->block_table ? st->max_blocks : 1,
+                 st->block_table ? st->n_blocks : 0};
 }
 
 int finish_launch()
@@ -1860,6 +1957,16 @@ void launch(void (*kernel)(Args), int blocks, hipStream_t stream, const Args &a)
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, a);
 }
 
+// Picks the paged or the contiguous instance of a kernel template whose last parameter is PAGED;
+// the arguments after `a` are the kernel's name and its leading template arguments.
+#define LAUNCH_PAGED(blocks, stream, a, ...)                          \
+    do {                                                              \
+        if ((a).st.block_table)                                       \
+            launch(__VA_ARGS__, true>, blocks, stream, a);            \
+        else                                                          \
+            launch(__VA_ARGS__, false>, blocks, stream, a);           \
+    } while (0)
+
 template <int D, typename TIn, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
@@ -1869,18 +1976,18 @@ void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
     if constexpr (TM == 1) {
         if (a.threshold > 0) {
             if (st)
-                launch(kvb_step_kernel<D, TIn, 1, WREC, true, true, true>, blocks, stream, a);
+                LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, true);
             else
-                launch(kvb_step_kernel<D, TIn, 1, WREC, true, true, false>, blocks, stream, a);
+                LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, false);
             return;
         }
     }
     if (!a.st.state)
-        launch(kvb_step_kernel<D, TIn, TM, WREC, false, false, false>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, false, false, false);
     else if (st)
-        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false, true>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, true);
     else
-        launch(kvb_step_kernel<D, TIn, TM, WREC, true, false, false>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, false);
 }
 
 template <int D, typename TIn, int TM>
@@ -1900,11 +2007,11 @@ template <int WREC>
 void launch_verify_mfma(const StepArgs &a, int blocks, hipStream_t stream)
 {
     if (!a.st.state)
-        launch(kvb_verify_mfma_kernel<WREC, false, false>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, false, false);
     else if (a.stream_state)
-        launch(kvb_verify_mfma_kernel<WREC, true, true>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, true, true);
     else
-        launch(kvb_verify_mfma_kernel<WREC, true, false>, blocks, stream, a);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, true, false);
 }
 
 template <int D, typename TIn>
@@ -2025,7 +2132,7 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
     CompactArgs a{dev_store(store), slot, path, path_len, shape->Hk, shape->Hv, shape->cap, T};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    rc = dispatch(shape, [&]<int D, typename TIn>() { launch(kvb_compact_kernel<D, TIn>, blocks, hs, a); });
+    rc = dispatch(shape, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, hs, a, kvb_compact_kernel<D, TIn); });
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
@@ -2047,7 +2154,7 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     rc = dispatch(shape, [&]<int D, typename TIn>() {
-        launch(kvb_flush_kernel<D, TIn>, blocks, hs, a);
+        LAUNCH_PAGED(blocks, hs, a, kvb_flush_kernel<D, TIn);
     });
     if (rc != KVB_OK)
         return rc;
@@ -2075,11 +2182,14 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (shape->dk == 128 && shape->in_dtype == KVB_BF16) {
-        launch(kvb_direct_mfma_kernel, blocks, hs, a);
+        if (a.st.block_table)
+            launch(kvb_direct_mfma_kernel<true>, blocks, hs, a);
+        else
+            launch(kvb_direct_mfma_kernel<false>, blocks, hs, a);
         return finish_launch();
     }
     rc = dispatch(shape, [&]<int D, typename TIn>() {
-        launch(kvb_direct_kernel<D, TIn>, blocks, hs, a);
+        LAUNCH_PAGED(blocks, hs, a, kvb_direct_kernel<D, TIn);
     });
     if (rc != KVB_OK)
         return rc;

@@ -33,7 +33,9 @@ class KvbShape(ctypes.Structure):
 class KvbStore(ctypes.Structure):
     _fields_ = [("state", ctypes.c_void_p), ("buf_k", ctypes.c_void_p), ("buf_u", ctypes.c_void_p),
                 ("buf_G", ctypes.c_void_p), ("fill", ctypes.c_void_p), ("status", ctypes.c_void_p),
-                ("n_slots", ctypes.c_int32), ("flags", ctypes.c_int32)]
+                ("n_slots", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("block_size", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("n_blocks", ctypes.c_int32)]
 
 
 class KvbError(RuntimeError):
@@ -100,8 +102,10 @@ def shape(B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, out_dtype=F32):
     return KvbShape(B, Hk, Hv, dk, dv, cap, in_dtype, out_dtype, scale)
 
 
-def store(state, buf_k, buf_u, buf_G, fill, status, n_slots, flags=0):
-    return KvbStore(_ptr(state), _ptr(buf_k), _ptr(buf_u), _ptr(buf_G), _ptr(fill), _ptr(status), n_slots, flags)
+def store(state, buf_k, buf_u, buf_G, fill, status, n_slots, flags=0, block_table=None, block_size=0,
+          max_blocks=0, n_blocks=0):
+    return KvbStore(_ptr(state), _ptr(buf_k), _ptr(buf_u), _ptr(buf_G), _ptr(fill), _ptr(status), n_slots, flags,
+                    _ptr(block_table), block_size, max_blocks, n_blocks)
 
 
 def strerror(code):
@@ -208,19 +212,48 @@ class DeviceStore:
     """Caller-side holder of the device arrays of include/kvb.h's kvb_store, allocated
     with PyTorch (memory plumbing only)."""
 
-    def __init__(self, n_slots, Hk, Hv, dk, dv, cap, in_dtype, device="cuda", with_state=True):
+    def __init__(self, n_slots, Hk, Hv, dk, dv, cap, in_dtype, device="cuda", with_state=True,
+                 block_size=None, n_blocks=None, block_table=None):
+        """block_size given: paged record buffers, pools of n_blocks blocks and a block table
+        [n_slots, ceil(cap / block_size)] (block_table: an int array of that shape; default
+        slot s takes the blocks s*mb .. s*mb+mb-1)."""
         import torch
         kd = torch.bfloat16 if in_dtype == BF16 else torch.float32
         self.n_slots, self.Hk, self.Hv, self.dk, self.dv, self.cap = n_slots, Hk, Hv, dk, dv, cap
         self.in_dtype = in_dtype
         self.state = torch.zeros((n_slots, Hv, dk, dv), dtype=torch.float32, device=device) \
             if with_state else None
-        self.buf_k = torch.zeros((n_slots, Hk, cap, dk), dtype=kd, device=device)
-        self.buf_u = torch.zeros((n_slots, Hv, cap, dv), dtype=torch.float32, device=device)
-        self.buf_G = torch.zeros((n_slots, Hv, cap), dtype=torch.float32, device=device)
+        self.block_size = block_size
+        if block_size:
+            self.max_blocks = -(-cap // block_size)
+            self.n_blocks = n_blocks if n_blocks else n_slots * self.max_blocks
+            if block_table is None:
+                block_table = torch.arange(n_slots * self.max_blocks).reshape(n_slots, self.max_blocks)
+            self.block_table = torch.as_tensor(block_table).to(dtype=torch.int32, device=device).contiguous()
+            assert tuple(self.block_table.shape) == (n_slots, self.max_blocks)
+            nb, per = self.n_blocks, block_size
+        else:
+            self.block_table, self.max_blocks, self.n_blocks = None, 0, 0
+            nb, per = n_slots, cap
+        self.buf_k = torch.zeros((nb, Hk, per, dk), dtype=kd, device=device)
+        self.buf_u = torch.zeros((nb, Hv, per, dv), dtype=torch.float32, device=device)
+        self.buf_G = torch.zeros((nb, Hv, per), dtype=torch.float32, device=device)
         self.fill = torch.zeros((n_slots,), dtype=torch.int32, device=device)
         self.status = torch.zeros((n_slots,), dtype=torch.int32, device=device)
 
     def c(self, with_state=True, flags=0):
         return store(self.state if with_state else None, self.buf_k, self.buf_u, self.buf_G, self.fill,
-                     self.status, self.n_slots, flags)
+                     self.status, self.n_slots, flags, self.block_table, self.block_size or 0,
+                     self.max_blocks, self.n_blocks)
+
+    def records(self, slot, lo, hi):
+        """(k [Hk,n,dk], u [Hv,n,dv], G [Hv,n]) of records lo..hi-1 of a slot, through the block
+        table if there is one (test and debugging aid; copies)."""
+        import torch
+        if not self.block_size:
+            return self.buf_k[slot, :, lo:hi], self.buf_u[slot, :, lo:hi], self.buf_G[slot, :, lo:hi]
+        ls = torch.arange(lo, hi, device=self.fill.device)
+        blk = self.block_table[slot, ls // self.block_size].long()
+        off = ls % self.block_size
+        return self.buf_k[blk, :, off].transpose(0, 1), self.buf_u[blk, :, off].transpose(0, 1), \
+            self.buf_G[blk, :, off].transpose(0, 1)

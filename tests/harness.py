@@ -45,11 +45,24 @@ class Layer:
     """One GDN layer's device store plus the call wrappers."""
 
     def __init__(self, B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, n_slots=None, slots=None,
-                 with_state=True, device="cuda"):
+                 with_state=True, device="cuda", block_size=None):
+        """block_size: paged record buffers; the blocks of the requests are then dealt at random
+        from a pool with a few spare blocks, which must stay untouched (checked by spare_clean)."""
         self.B, self.Hk, self.Hv, self.dk, self.dv, self.cap = B, Hk, Hv, dk, dv, cap
         self.in_dtype, self.scale, self.device = in_dtype, scale, device
         self.n_slots = n_slots if n_slots is not None else B
-        self.ds = kvb.DeviceStore(self.n_slots, Hk, Hv, dk, dv, cap, DT[in_dtype], device, with_state)
+        if block_size:
+            mb = -(-cap // block_size)
+            nb = self.n_slots * mb + 3
+            perm = np.random.default_rng(cap * 131 + block_size).permutation(nb)
+            self.spare = perm[self.n_slots * mb:]
+            table = perm[:self.n_slots * mb].reshape(self.n_slots, mb)
+            self.ds = kvb.DeviceStore(self.n_slots, Hk, Hv, dk, dv, cap, DT[in_dtype], device, with_state,
+                                      block_size=block_size, n_blocks=nb, block_table=table)
+            self.ds.buf_u[torch.from_numpy(self.spare).to(device)] = 12345.0
+        else:
+            self.spare = None
+            self.ds = kvb.DeviceStore(self.n_slots, Hk, Hv, dk, dv, cap, DT[in_dtype], device, with_state)
         self.slots_np = np.arange(B, dtype=np.int32) if slots is None else np.asarray(slots, np.int32)
         self.slot = dev(self.slots_np)
         self.with_state = with_state
@@ -57,6 +70,26 @@ class Layer:
     def shape(self, B=None):
         return kvb.shape(self.B if B is None else B, self.Hk, self.Hv, self.dk, self.dv, self.cap,
                          DT[self.in_dtype], self.scale)
+
+    def spare_clean(self):
+        """True if no call has written into a block that belongs to no request."""
+        if self.spare is None:
+            return True
+        sp = torch.from_numpy(self.spare).to(self.device)
+        return bool((self.ds.buf_u[sp] == 12345.0).all()) and bool((self.ds.buf_G[sp] == 0).all())
+
+    def u_at(self, pos):
+        """u records at position pos[b] (an int or an int array [B]) of every request: [B,Hv,dv]."""
+        sl = self.slot.long()
+        pos = torch.as_tensor(pos, device=self.device).expand(self.B).long()
+        if not self.ds.block_size:
+            return self.ds.buf_u[sl, :, pos]
+        blk = self.ds.block_table[sl, pos // self.ds.block_size].long()
+        return self.ds.buf_u[blk, :, pos % self.ds.block_size]
+
+    def u_records(self, b, lo, hi):
+        """u records lo..hi-1 of request b as numpy [Hv, n, dv]."""
+        return self.ds.records(int(self.slots_np[b]), lo, hi)[1].cpu().numpy()
 
     def set_state(self, S_f32):
         self.ds.state[self.slot.long()] = dev(S_f32)
@@ -129,7 +162,7 @@ def run_decode(layer, S0, tok, C, flush_every_step=True, final_flush=True, fused
         else:
             layer.decode(step_view(dtok, t), o_t)
         out[:, t] = o_t
-        u_rec[:, t] = layer.ds.buf_u[sl, :, f_before]
+        u_rec[:, t] = layer.u_at(f_before)
         if flush_every_step and not fused:
             layer.flush(C)
         fills.append(int(layer.ds.fill[sl[0]].item()))

@@ -36,7 +36,9 @@ def test_version_and_error_strings():
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(kvb.KvbShape) == 9 * 4
     assert kvb.KvbStore.n_slots.offset == 6 * 8 and kvb.KvbStore.flags.offset == 6 * 8 + 4
-    assert ctypes.sizeof(kvb.KvbStore) == 7 * 8
+    assert kvb.KvbStore.block_table.offset == 7 * 8 and kvb.KvbStore.block_size.offset == 8 * 8
+    assert kvb.KvbStore.n_blocks.offset == 8 * 8 + 8
+    assert ctypes.sizeof(kvb.KvbStore) == 10 * 8
 
 
 A = 0x1000  # a fake, well-aligned "device address": validation must fail before it is used
@@ -101,6 +103,17 @@ def test_flush_verify_direct_argument_ranges():
     for Lmax in (0, 17, 65):
         assert kvb.kvb_direct(sh, st, A, A, Lmax, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
     assert kvb.kvb_direct(sh, st, A, None, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
+
+
+def test_paged_store_argument_ranges():
+    sh = kvb.shape(**GOOD)   # cap = 16
+    ok = dict(block_table=A, block_size=8, max_blocks=2, n_blocks=64)
+    assert _decode(kvb.shape(**{**GOOD, "B": 0}), _store(**ok)) == kvb.OK
+    for bad in (dict(block_size=12), dict(block_size=4), dict(block_size=256), dict(max_blocks=1),
+                dict(max_blocks=0), dict(max_blocks=17), dict(n_blocks=0), dict(block_table=A + 2)):
+        assert _decode(sh, _store(**{**ok, **bad})) == kvb.EINVAL, bad
+    # without a table the three sizes are ignored
+    assert _decode(kvb.shape(**{**GOOD, "B": 0}), _store(block_size=3, max_blocks=99, n_blocks=-1)) == kvb.OK
 
 
 def test_tree_verify_and_compact_argument_ranges():

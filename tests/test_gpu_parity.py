@@ -93,7 +93,7 @@ def test_qwen3next_decode_full(fused):
 
 
 # --------------------------------------------------------------------------- verify
-def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=False):
+def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=False, block_size=None):
     rng = np.random.default_rng(seed)
     fill_hi = C - 1 if fill_hi is None else fill_hi
     S0 = np.zeros((B, Hv, d, d), np.float32) if kv_only else H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
@@ -101,7 +101,7 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     wtok = synth.token_stream(rng, B, max(1, fill_hi), Hk, Hv, d, d, in_dtype)
     vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
     acc = synth.accepted_lengths(rng, B, T)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size)
     lay.set_state(S0)
     ragged_warmup(lay, fills, wtok)
     # oracle: true state after the warm-up tokens
@@ -116,7 +116,7 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     assert np.array_equal(lay.fill(), fills), "kvb_verify changed fill"
     e_out = H.rel_err(out.cpu().numpy(), o_ref)
     # draft records sit at f..f+T-1
-    u_got = np.stack([lay.ds.buf_u[b, :, fills[b]:fills[b] + T].cpu().numpy() for b in range(B)])  # [B,Hv,T,d]
+    u_got = np.stack([lay.u_records(b, fills[b], fills[b] + T) for b in range(B)])  # [B,Hv,T,d]
     e_u = H.rel_err(u_got.transpose(0, 2, 1, 3), u_ref)
     # commit accepted prefix; flush the requests that reached C; then fold everything
     lay.flush(C, accepted=H.dev(acc))
@@ -127,10 +127,11 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     torch.cuda.synchronize()
     e_S = H.rel_err(lay.get_state(), S_acc)
     assert not lay.status().any()
+    assert lay.spare_clean()
     return e_out, e_u, e_S
 
 
-def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=False):
+def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=False, block_size=None):
     """kvb_verify_tree + kvb_compact + kvb_flush against the oracle run along every root path."""
     rng = np.random.default_rng(seed)
     fill_hi = min(C - 1, cap - T)
@@ -140,7 +141,7 @@ def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=F
     vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
     parent = synth.draft_trees(rng, B, T, kind)
     leaf, path, plen = synth.accepted_paths(rng, parent)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size)
     lay.set_state(S0)
     ragged_warmup(lay, fills, wtok)
     _, _, S_true, _ = oracle.gdn_sequence(S0, wtok["q"], wtok["k"], wtok["v"], wtok["g"], wtok["beta"], lens=fills)
@@ -153,7 +154,7 @@ def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=F
     assert torch.equal(lay.ds.state, state_before), "kvb_verify_tree wrote the state"
     assert np.array_equal(lay.fill(), fills), "kvb_verify_tree changed fill"
     e_out = H.rel_err(out.cpu().numpy(), o_ref)
-    u_got = np.stack([lay.ds.buf_u[b, :, fills[b]:fills[b] + T].cpu().numpy() for b in range(B)])
+    u_got = np.stack([lay.u_records(b, fills[b], fills[b] + T) for b in range(B)])
     e_u = H.rel_err(u_got.transpose(0, 2, 1, 3), u_ref)
     # accepted root path to the front, commit it, fold everything
     lay.compact(T, H.dev(path), H.dev(plen))
@@ -165,6 +166,7 @@ def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=F
     torch.cuda.synchronize()
     e_S = H.rel_err(lay.get_state(), S_acc)
     assert not lay.status().any()
+    assert lay.spare_clean()
     return e_out, e_u, e_S
 
 
@@ -274,12 +276,12 @@ def test_spec_verify_tree_full():
 
 
 # --------------------------------------------------------------------------- direct
-def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True):
+def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True, block_size=None):
     rng = np.random.default_rng(seed)
     if lens is None:
         lens = synth.context_lengths(rng, B, 1, Lmax)
     tok = synth.token_stream(rng, B, Lmax, Hk, Hv, d, d, in_dtype)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False, block_size=block_size)
     lay.ds.fill.fill_(3)          # stale fill must be discarded
     out = torch.full((B, Lmax, Hv, d), float("nan"), dtype=torch.float32, device="cuda")
     lay.direct(H.dev(lens), Lmax, H.upload_tokens(tok, in_dtype), out)
@@ -289,7 +291,7 @@ def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode
     valid = ~np.isnan(o_ref)
     assert np.all(np.isnan(got[~valid])), "rows >= len were written"
     e_out = H.rel_err(got[valid], o_ref[valid])
-    u_got = lay.ds.buf_u[:, :, :Lmax].cpu().numpy().transpose(0, 2, 1, 3)
+    u_got = np.stack([lay.u_records(b, 0, Lmax) for b in range(B)]).transpose(0, 2, 1, 3)
     e_u = H.rel_err(u_got[valid], u_ref[valid])
     assert np.array_equal(lay.fill(), lens)
     e_dec = 0.0
@@ -310,6 +312,7 @@ def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode
     torch.cuda.synchronize()
     e_S = H.rel_err(lay.get_state(), S_ref)
     assert not lay.fill().any()
+    assert lay.spare_clean()
     return e_out, e_u, e_dec, e_S
 
 
@@ -705,3 +708,59 @@ def test_kv_only_verify_and_stream_hint_do_not_change_results():
         res.append((outs.clone(), vout.clone(), lay.ds.state.clone(), lay.ds.buf_u.clone()))
     for x, y in zip(*res):
         assert torch.equal(x, y)
+
+
+# --------------------------------------------------------------------------- paged record buffers
+@pytest.mark.parametrize("d, in_dtype, C, block_size, fused", [
+    (128, "bf16", 16, 16, True), (128, "bf16", 16, 8, True), (128, "bf16", 16, 8, False),
+    (128, "bf16", 64, 16, True), (128, "bf16", 40, 8, False), (64, "bf16", 24, 8, True),
+    (32, "f32", 16, 8, True), (128, "f32", 12, 16, False),
+])
+def test_paged_decode_flush(d, in_dtype, C, block_size, fused):
+    """Blocks of 8 or 16 records dealt at random from a shared pool (Sec. 3.1): same results as the
+    contiguous layout, nothing written outside the request's own blocks."""
+    rng = np.random.default_rng(700 + d + C + block_size)
+    B, Hk, Hv, steps = 3, 1, 2, 2 * C + 3
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 8)
+    tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, block_size=block_size)
+    o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=fused)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("paged d=%d %s C=%d block=%d fused=%s rel err out/u/state: %.2e %.2e %.2e" % ((d, in_dtype, C, block_size, fused) + e))
+    assert max(e) < H.TOL[in_dtype]
+    assert lay.spare_clean() and not lay.status().any()
+
+
+def test_paged_verify_tree_and_direct():
+    e = _verify_case(B=6, Hk=2, Hv=4, d=128, C=16, cap=19, T=4, in_dtype="bf16", seed=710, block_size=8)
+    assert max(e) < H.TOL["bf16"], e
+    e = _verify_case(B=3, Hk=2, Hv=4, d=128, C=64, cap=71, T=8, in_dtype="bf16", seed=711, fill_hi=63, block_size=16)
+    assert max(e) < H.TOL["bf16"], e
+    e = _verify_case(B=2, Hk=1, Hv=2, d=32, C=8, cap=11, T=4, in_dtype="f32", seed=712, block_size=8)
+    assert max(e) < H.TOL["f32"], e
+    e = _tree_case(B=5, Hk=2, Hv=4, d=128, C=16, cap=23, T=8, in_dtype="bf16", seed=713, block_size=8)
+    assert max(e) < H.TOL["bf16"], e
+    e = _tree_case(B=3, Hk=2, Hv=2, d=64, C=8, cap=16, T=8, in_dtype="bf16", seed=714, block_size=16)
+    assert max(e) < H.TOL["bf16"], e
+    e = _direct_case(B=5, Hk=2, Hv=4, d=128, Lmax=64, cap=80, in_dtype="bf16", seed=715, block_size=16)
+    assert max(e) < H.TOL["bf16"], e
+    e = _direct_case(B=4, Hk=1, Hv=2, d=128, Lmax=37, cap=40, in_dtype="bf16", seed=716, block_size=8)
+    assert max(e) < H.TOL["bf16"], e
+    e = _direct_case(B=3, Hk=1, Hv=2, d=32, Lmax=16, cap=24, in_dtype="f32", seed=717, block_size=8)
+    assert max(e) < H.TOL["f32"], e
+
+
+def test_paged_qwen3next_decode_full():
+    """Workload 2 at full size with 16-record blocks from a shuffled pool, fused step."""
+    w = synth.WORKLOADS["qwen3next_decode"]
+    rng = np.random.default_rng(w.seed)
+    S0 = H.prefix_state(rng, w.B, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype, w.prefix)
+    tok = synth.token_stream(rng, w.B, 64, w.Hk, w.Hv, w.dk, w.dv, w.in_dtype)
+    lay = H.Layer(w.B, w.Hk, w.Hv, w.dk, w.dv, cap=w.cap, in_dtype=w.in_dtype, block_size=16)
+    o, u, S, _ = H.run_decode(lay, S0, tok, w.C, fused=True)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("paged qwen3next_decode rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    assert lay.spare_clean()
