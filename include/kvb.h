@@ -145,8 +145,10 @@ int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32
  * Sec. 3.3 Eq. 8).  For request b: m = fill + (accepted ? accepted[b] : 0); if
  * m >= threshold and m > 0:  S <- exp(G_{m-1}) S + sum_l exp(G_{m-1} - G_l) k_l^T u_l
  * and fill = 0; otherwise fill = m and the state is untouched.  Besides
- * kvb_decode_flush the only call that writes `state` (which must not be NULL).
+ * kvb_decode_flush the only call that writes `state`.
  * On a zeroed state this is the KV-only -> state transition of Sec. 3.4.
+ * state == NULL (a KV-only context): nothing is folded, the call only commits the accepted
+ * drafts of a preceding kvb_verify (fill = m); `accepted` must then be given.
  *   accepted  device int32 [B] (each 0..T of the preceding kvb_verify) or NULL
  *   threshold 1..cap; 1 flushes every non-empty buffer
  * m > cap sets KVB_STATUS_OVERFLOW and is treated as cap.

@@ -876,7 +876,8 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
         if (tid == 0 && a.st.status)
             atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
     }
-    const bool do_flush = m >= a.threshold && m > 0;
+    // (no state: a KV-only context, Sec. 3.4 -- the call then only commits accepted drafts)
+    const bool do_flush = a.st.state != nullptr && m >= a.threshold && m > 0;
     if (!do_flush) {
         if (m != f && tid == 0)   // fill only moves when something was accepted
             publish_fill(&a.st.fill[s], a.Hv, m);
@@ -2144,7 +2145,9 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
     int rc = check_common(shape, store, slot);
     if (rc != KVB_OK)
         return rc;
-    if (!store->state || !aligned(accepted, 4))
+    if (!aligned(accepted, 4))
+        return KVB_EINVAL;
+    if (!store->state && !accepted)   // nothing to fold into and nothing to commit
         return KVB_EINVAL;
     if (threshold < 1 || threshold > shape->cap)
         return KVB_EINVAL;

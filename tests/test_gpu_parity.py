@@ -764,3 +764,30 @@ def test_paged_qwen3next_decode_full():
     say("paged qwen3next_decode rel err out/u/state: %.2e %.2e %.2e" % e)
     assert max(e) < H.TOL["bf16"]
     assert lay.spare_clean()
+
+
+def test_kv_only_speculative_decoding_commits_without_a_state():
+    """A KV-only context (no state at all) verified in chunks of drafts: kvb_verify with a NULL
+    state, then kvb_flush with a NULL state, which only commits the accepted prefix (Sec. 3.3 on
+    top of Sec. 3.4).  Outputs against the recurrence from a zero state."""
+    rng = np.random.default_rng(160)
+    B, Hk, Hv, d, T, rounds, cap = 4, 2, 4, 128, 4, 5, 32
+    tok = synth.token_stream(rng, B, T * rounds, Hk, Hv, d, d, "bf16")
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype="bf16", with_state=False)
+    S = np.zeros((B, Hv, d, d))
+    pos = np.zeros(B, np.int64)          # tokens committed so far per request
+    worst = 0.0
+    for r_ in range(rounds):
+        idx = pos[:, None] + np.arange(T)[None, :]
+        chunk = {n: np.take_along_axis(x, idx.reshape((B, T) + (1,) * (x.ndim - 2)), axis=1) for n, x in tok.items()}
+        acc = synth.accepted_lengths(rng, B, T)
+        o_ref, _, S = oracle.kvb_verify_expected(S, chunk["q"], chunk["k"], chunk["v"], chunk["g"], chunk["beta"], acc)
+        out = torch.empty((B, T, Hv, d), dtype=torch.float32, device="cuda")
+        lay.verify(T, H.upload_tokens(chunk, "bf16"), out, use_state=False)
+        kvb.kvb_flush(lay.shape(), lay.ds.c(False), lay.slot, H.dev(acc), 1)
+        torch.cuda.synchronize()
+        worst = max(worst, H.rel_err(out.cpu().numpy(), o_ref))
+        pos += acc
+        assert np.array_equal(lay.fill(), pos)
+    assert worst < H.TOL["bf16"], worst
+    assert not lay.status().any()
