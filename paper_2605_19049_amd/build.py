@@ -1,14 +1,18 @@
-"""Build step: compile csrc/kvb.hip for gfx950 into libkvb.so next to this file.
+"""Build step: compile csrc/*.hip for gfx950 into libkvb.so next to this file.
 
-hipcc cross-compiles without a GPU.  Run as ``python -m paper_2605_19049_amd.build``.
+One object per translation unit, compiled side by side, then one link.  hipcc cross-compiles
+without a GPU.  Run as ``python -m paper_2605_19049_amd.build``.
 """
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "kvb.hip")
+CSRC = os.path.join(HERE, "csrc")
+SOURCES = ["kvb_api.hip", "kvb_step_bf16.hip", "kvb_step_f32.hip", "kvb_verify.hip", "kvb_flush.hip", "kvb_direct.hip"]
 LIB = os.path.join(HERE, "libkvb.so")
 
 HIPCC_FLAGS = [
@@ -18,26 +22,49 @@ HIPCC_FLAGS = [
     # keep the single-lane ticket atomics as written: the wave-aggregating rewrite reads
     # the result back at once, which would make the wave wait for its whole state tile
     "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
-    "-shared", "-fPIC", "-I" + os.path.join(ROOT, "include"),
+    "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
+
+
+def _clean(text):
+    # the host pass warns that it does not know the packed-fp32 feature: harmless
+    return "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l)
 
 
 def build_lib(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".%d.tmp" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + os.environ.get("KVB_EXTRA_HIPCC_FLAGS", "").split() + ["-o", tmp, SRC]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    # the host pass warns that it does not know the packed-fp32 feature: harmless
-    out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if proc.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
-    os.replace(tmp, LIB)
+    extra = os.environ.get("KVB_EXTRA_HIPCC_FLAGS", "").split()
+    work = tempfile.mkdtemp(prefix="kvb_build_")
+    try:
+        procs = []
+        for src in SOURCES:
+            obj = os.path.join(work, src + ".o")
+            cmd = [hipcc] + HIPCC_FLAGS + extra + ["-c", "-o", obj, os.path.join(CSRC, src)]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs, failed = [], []
+        for src, obj, proc in procs:
+            out = _clean(proc.communicate()[0])
+            if proc.returncode != 0:
+                failed.append("%s:\n%s" % (src, out))
+            elif verbose and out.strip():
+                print(out)
+            objs.append(obj)
+        if failed:
+            raise RuntimeError("hipcc failed:\n" + "\n".join(failed))
+        tmp = os.path.join(work, "libkvb.so")
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+        if verbose:
+            print(" ".join(link), flush=True)
+        proc = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("link failed:\n" + _clean(proc.stdout))
+        final_tmp = LIB + ".%d.tmp" % os.getpid()
+        shutil.copyfile(tmp, final_tmp)
+        os.replace(final_tmp, LIB)
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
     return LIB
 
 

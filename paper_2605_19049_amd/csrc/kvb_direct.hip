@@ -1,0 +1,454 @@
+// kvb_direct: kvb_direct_mfma_kernel (bf16, d = 128) and kvb_direct_kernel (other types and head sizes).
+#include "kvb_device.h"
+
+namespace kvb_impl {
+
+// ---------------------------------------------------------------------------
+// kvb_direct: the parallel form, Eq. 13, from a zero state.
+//   cK[i][l] = Gamma_il (k_i.k_l) (l < i)     cQ[i][l] = Gamma_il (q_i.k_l) (l <= i)
+//   u_i = beta_i ( v_i - sum_{l<i} cK[i][l] u_l )       (row i of A Diag(beta) V)
+//   o_i = scale * sum_{l<=i} cQ[i][l] u_l
+// ---------------------------------------------------------------------------
+template <int D, typename TIn, bool PAGED>
+__global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
+{
+    constexpr int LM = KVB_MAX_DIRECT_LEN;
+    __shared__ float sK[LM][D + 1];
+    __shared__ float sQ[LM][D + 1];
+    __shared__ float cK[LM][LM + 1];
+    __shared__ float cQ[LM][LM + 1];
+    __shared__ float sU[LM][D];
+    __shared__ float sG[LM];
+    __shared__ float sB[LM];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
+
+    const int tid = threadIdx.x;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int hk = h / r;
+    const int Lmax = a.Lmax;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    int L = a.len[b];
+    if (L < 0 || L > Lmax) {
+        L = Lmax;
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+    }
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[tid / 64], tid % 64, load_block_id<PAGED>(a.st, s, tid % 64));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
+    const TIn *qin = static_cast<const TIn *>(a.q);
+    const TIn *kin = static_cast<const TIn *>(a.k);
+    const TIn *vin = static_cast<const TIn *>(a.v);
+
+    for (int idx = tid; idx < L * D; idx += NT) {
+        const int i = idx / D, e = idx % D;
+        const size_t o = (((size_t)b * Lmax + i) * a.Hk + hk) * D + e;
+        sK[i][e] = to_f32(kin[o]);
+        sQ[i][e] = to_f32(qin[o]);
+    }
+    if (tid < L) {
+        float run = 0.0f;
+        for (int t = 0; t <= tid; ++t)
+            run += a.g[((size_t)b * Lmax + t) * a.Hv + h];
+        sG[tid] = run;
+        sB[tid] = a.beta[((size_t)b * Lmax + tid) * a.Hv + h];
+    }
+    __syncthreads();
+
+    for (int p = tid; p < L * L; p += NT) {
+        const int i = p / L, l = p % L;
+        if (l <= i) {
+            float dkk = 0.0f, dqk = 0.0f;
+#pragma unroll 8
+            for (int e = 0; e < D; ++e) {
+                const float kl = sK[l][e];
+                dkk = fmaf(sK[i][e], kl, dkk);
+                dqk = fmaf(sQ[i][e], kl, dqk);
+            }
+            const float gam = expf(sG[i] - sG[l]);
+            cK[i][l] = gam * dkk;
+            cQ[i][l] = gam * dqk;
+        }
+    }
+    __syncthreads();
+
+    if (tid < D) {
+        for (int i = 0; i < L; ++i) {
+            const size_t row = ((size_t)b * Lmax + i) * a.Hv + h;
+            float acc = to_f32(vin[row * D + tid]);
+            float o = 0.0f;
+            for (int l = 0; l < i; ++l) {
+                const float ul = sU[l][tid];
+                acc = fmaf(-cK[i][l], ul, acc);
+                o = fmaf(cQ[i][l], ul, o);
+            }
+            const float ui = sB[i] * acc;
+            sU[i][tid] = ui;
+            o = fmaf(cQ[i][i], ui, o);
+            a.out[row * D + tid] = a.scale * o;
+            a.st.buf_u[ru(i) * D + tid] = ui;
+        }
+    }
+    if (tid < L)
+        a.st.buf_G[ru(tid)] = sG[tid];
+    if (h % r == 0) {
+        TIn *kb = static_cast<TIn *>(a.st.buf_k);
+        for (int idx = tid; idx < L * D; idx += NT) {
+            const int i = idx / D, e = idx % D;
+            kb[rk(i) * D + e] = kin[(((size_t)b * Lmax + i) * a.Hk + hk) * D + e];
+        }
+    }
+    if (h == 0 && tid == 0)
+        a.st.fill[s] = L;
+}
+
+// ---------------------------------------------------------------------------
+// kvb_direct for bf16 inputs and d = 128, on the matrix cores throughout.
+//
+// The context is cut into blocks of 16 rows.  With N_il = beta_i Gamma_il (k_i.k_l) (l < i)
+// and M_il = Gamma_il (q_i.k_l) (l <= i) the parallel form (Eq. 13) is
+//     (I + N) U = Diag(beta) V,      O = M U,
+// solved block row by block row:  U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),
+// T_d = (I + N_dd)^-1 = (I - N)(I + N^2)(I + N^4)(I + N^8)   (N_dd is strictly lower, N^16 = 0),
+// O_d = sum_{e<=d} M_de U_e.
+//   * Gram tiles (k.k, q.k over dk = 128, bf16 operands): v_mfma_f32_16x16x32_bf16.
+//   * everything after that has fp32 operands: v_mfma_f32_16x16x4_f32 (exact products).
+//
+// Register chaining.  Call "A-form" of a 16x16 matrix X the register layout in which lane l
+// holds X[l%16][4*(l/16)+v], v = 0..3, and "B-form" the one with X[4*(l/16)+v][l%16].  An
+// MFMA result is in B-form; feeding four k-steps with (a = xa[v], b = yb[v]) gives the
+// B-form of X Y, and swapping the operands, (a = yb[v], b = xa[v]), gives the A-form of X Y.
+// A Gram tile computed as (rows of block e) x (rows of block d) lands directly in A-form of
+// the (d, e) tile, so no value ever needs to move between lanes: tiles shared between waves
+// go through LDS as whole per-lane float4s.  Each wave owns 32 dv columns (two column tiles).
+// ---------------------------------------------------------------------------
+
+// B-form of X Y from X in A-form and Y in B-form (swap the arguments for the A-form of X Y).
+__device__ __forceinline__ f32x4_t mm16(const f32x4_t &xa, const f32x4_t &yb, f32x4_t acc)
+{
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[v], yb[v], acc, 0, 0, 0);
+    return acc;
+}
+
+// exp for arguments that are differences of cumulative log decays (<= 0, a few tens at
+// most): one multiply and the hardware exp2; relative error about |x| * 2^-23, far inside
+// the 2e-3 bound of the bf16 paths that use it.
+__device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
+
+template <typename... Ts>
+constexpr uint32_t pack2(Ts... xs)
+{
+    uint32_t r = 0;
+    int sh = 0;
+    ((r |= (uint32_t)xs << sh, sh += 2), ...);
+    return r;
+}
+
+// Raw Gram tile from rows staged in LDS (row stride GS bf16 elements): lane l reads row l%16
+// of the A-side block and of the B-side block at k = 8*(l/16) + 32*step.  acc[v] =
+// (A-side row 4*(l/16)+v) . (B-side row l%16), i.e. the A-form of the (B-block, A-block) tile.
+template <int GS>
+__device__ __forceinline__ f32x4_t gram16(const bf16_t *arow, const bf16_t *brow, int lq)
+{
+    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
+        const uint4 bv = *reinterpret_cast<const uint4 *>(brow + 8 * lq + 32 * st);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                    __builtin_bit_cast(bf16x8_t, bv), c, 0, 0, 0);
+    }
+    return c;
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void kvb_direct_mfma_kernel(
+    const DirectArgs a)
+{
+    constexpr int D = 128;
+    constexpr int LM = KVB_MAX_DIRECT_LEN;
+    constexpr int NB = LM / 16;                 // blocks of 16 rows (4)
+    constexpr int NLOW = NB * (NB + 1) / 2;     // lower-triangular block pairs (10)
+    constexpr int GS = D + 8;                   // LDS row stride of the staged keys / queries (272 B:
+                                                // consecutive rows start 4 banks apart)
+    static_assert(NB == NW, "one diagonal block per wave");
+    // One LDS region, used twice: first the staged K and Q rows (bf16), then, once every
+    // raw Gram tile sits in registers, the weighted tiles in A-form (one float4 per lane):
+    // -N_de (d > e), M_de (d >= e), T_d.
+    constexpr int STAGE_BYTES = LM * GS * 2;
+    constexpr int TILE_BYTES = (2 * NLOW + NB) * 64 * 16;
+    __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
+    __shared__ float sG[LM];
+    __shared__ float sB[LM];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
+    bf16_t *sK = reinterpret_cast<bf16_t *>(region);
+    float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
+    float4(*tM)[64] = tN + NLOW;
+    float4(*tT)[64] = tM + NLOW;
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int c16 = lane % 16, lq = lane / 16;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int hk = h / r;
+    const int Lmax = a.Lmax;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    int L = a.len[b];
+    if (L < 0 || L > Lmax) {
+        L = Lmax;
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+    }
+    if (L == 0) {
+        if (h == 0 && tid == 0)
+            a.st.fill[s] = 0;
+        return;
+    }
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
+    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
+    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
+    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const int nb = (L + 15) / 16;
+    auto tri = [](int d, int e) { return d * (d + 1) / 2 + e; };
+
+    // ---- all global loads of the workgroup, issued together ---------------------
+    // K and Q rows, 16 bytes per thread and pass (pass p = rows 16 p .. 16 p + 15)
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    u32x4_t kst[NB];
+    const int srow = tid / 16, sc8 = tid % 16;
+    // (uniform 64-bit base + 32-bit per-lane offset keeps the address arithmetic out of the VGPRs)
+    const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
+    const uint32_t qk_stride = (uint32_t)a.Hk * D, v_stride = (uint32_t)a.Hv * D;
+#pragma unroll
+    for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
+        const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
+        kst[p] = u32x4_t{0u, 0u, 0u, 0u};
+        if (p < nb)   // uniform
+            kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
+    }
+    // Q is not staged: the waves read the rows of their q.k tiles straight from memory in the
+    // operand layout of the matrix instruction (row 16 d + c16, k = 8 lq + 32 step); a block of
+    // 16 query rows is 4 KB and is shared by at most 4 tiles, so the repeats hit in the caches
+    // and the LDS footprint is that of K alone (5 workgroups per CU instead of 4).
+    // Tiles are dealt round-robin: t = wave + 4 n; t < 6 are k.k pairs, the rest q.k pairs.
+    constexpr uint32_t PDB = pack2(1, 2, 2, 3, 3, 3, 0, 1, 1, 2, 2, 2, 3, 3, 3, 3);
+    constexpr uint32_t PEB = pack2(0, 0, 1, 0, 1, 2, 0, 0, 1, 0, 1, 2, 0, 1, 2, 3);
+    auto PD = [](int t) { return (int)((PDB >> (2 * t)) & 3u); };
+    auto PE = [](int t) { return (int)((PEB >> (2 * t)) & 3u); };
+    u32x4_t qop[3][4];   // n = 1 (waves 2, 3 only), 2, 3
+#pragma unroll
+    for (int n = 1; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t);
+        const uint32_t o = (uint32_t)min(16 * d + c16, L - 1) * qk_stride + 8 * lq;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            qop[n - 1][st] = u32x4_t{0u, 0u, 0u, 0u};
+            if (t >= 6 && d < nb)   // uniform
+                qop[n - 1][st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
+        }
+    }
+    const int col2 = 32 * wave + 2 * c16;
+    // cumulative log decay (inclusive scan over the wave) and beta
+    if (wave == 0) {
+        float gv = lane < L ? a.g[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+        const float bv = lane < L ? a.beta[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_up(gv, off);
+            if (lane >= off)
+                gv += t;
+        }
+        sG[lane] = gv;
+        sB[lane] = bv;
+        if (lane < L)
+            a.st.buf_G[ru(lane)] = gv;
+    }
+    // stage K, Q; the thread that loaded a piece of K also appends it to the buffer
+    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k);
+#pragma unroll
+    for (int p = 0; p < NB; ++p) {
+        if (p < nb) {   // uniform
+            *reinterpret_cast<u32x4_t *>(sK + (16 * p + srow) * GS + 8 * sc8) = kst[p];
+            if (h % r == 0 && 16 * p + srow < L)
+                *reinterpret_cast<u32x4_t *>(kb + rk(16 * p + srow) * D + 8 * sc8) = kst[p];
+        }
+    }
+    __syncthreads();
+
+    // ---- raw Gram tiles: this wave's diagonal k.k tile and its share of the others ----
+    // off-diagonal k.k pairs (d > e): 6; q.k pairs (d >= e): 10
+    // (two bits per entry, packed: a table indexed by the wave number would live in scratch)
+    f32x4_t gdiag = {0.f, 0.f, 0.f, 0.f};
+    if (wave < nb)
+        gdiag = gram16<GS>(sK + (16 * wave + c16) * GS, sK + (16 * wave + c16) * GS, lq);
+    f32x4_t gsh[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t), e = PE(t);
+        gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (d < nb) {   // uniform
+            if (t < 6) {
+                gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
+            } else if (n > 0) {   // t >= 6 implies n >= 1
+                const bf16_t *arow = sK + (16 * e + c16) * GS;
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
+                    gsh[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, qop[n > 0 ? n - 1 : 0][st]),
+                        gsh[n], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();   // every wave is done with the staged rows: the region now takes the tiles
+
+    // v in B-form: rows 16 d + 4 lq + v, this lane's two adjacent columns 32 wave + 2 c16, + 1.
+    // Requested only now, when the registers of the staged rows are free again; the values
+    // are not needed before the substitution, two phases further down.
+    uint32_t v_raw[NB][4];
+#pragma unroll
+    for (int d = 0; d < NB; ++d)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            v_raw[d][v] = 0u;
+            if (d < nb)   // uniform
+                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+        }
+
+    // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int t = wave + NW * n, d = PD(t), e = PE(t);
+        if (d < nb) {
+            const int i = 16 * d + c16;
+            const bool isq = t >= 6;
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int l = 16 * e + 4 * lq + v;
+                const bool ok = i < L && (isq ? l <= i : l < i);
+                const float w = ok ? fast_exp(sG[i] - sG[l]) : 0.0f;
+                o[v] = (isq ? w : -sB[i] * w) * gsh[n][v];
+            }
+            const float4 o4 = make_float4(o[0], o[1], o[2], o[3]);
+            if (isq)
+                tM[tri(d, e)][lane] = o4;
+            else
+                tN[tri(d, e)][lane] = o4;
+        }
+    }
+    // T_d for d = wave.  The raw diagonal tile is symmetric, so the same registers give the
+    // A-form (row 16 d + c16, column 16 d + 4 lq + v) and the B-form (row and column swapped).
+    if (wave < nb) {
+        const int d = wave;
+        f32x4_t na, nbm, ia;   // N in both forms; identity mask (the same in both forms)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ia_i = 16 * d + c16, ia_l = 16 * d + 4 * lq + v;    // A-form indices
+            const int ib_i = ia_l, ib_l = ia_i;                            // B-form indices
+            const float wa = (ia_i < L && ia_l < ia_i) ? sB[ia_i] * fast_exp(sG[ia_i] - sG[ia_l]) : 0.0f;
+            const float wb = (ib_i < L && ib_l < ib_i) ? sB[ib_i] * fast_exp(sG[ib_i] - sG[ib_l]) : 0.0f;
+            na[v] = wa * gdiag[v];
+            nbm[v] = wb * gdiag[v];
+            ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
+        }
+        const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+        const f32x4_t n2b = mm16(na, nbm, z), n2a = mm16(nbm, na, z);
+        const f32x4_t n4b = mm16(n2a, n2b, z), n4a = mm16(n2b, n2a, z);
+        const f32x4_t n8b = mm16(n4a, n4b, z);
+        // A-form of (I - N)(I + N^2), then x (I + N^4), then x (I + N^8)
+        f32x4_t p = mm16(ia + n2b, ia - na, z);
+        p = mm16(ia + n4b, p, z);
+        p = mm16(ia + n8b, p, z);
+        tT[d][lane] = make_float4(p[0], p[1], p[2], p[3]);
+    }
+    __syncthreads();
+
+    // ---- block forward substitution and outputs, this wave's 32 columns ----------
+    // column tile c of the wave holds columns 32 wave + 2 n + c (n = 0..15): a lane's two
+    // tiles are adjacent columns, so v arrives as one 4-byte load and results leave as float2
+    f32x4_t U[NB][2];
+    float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
+    float *up = a.st.buf_u;
+#pragma unroll
+    for (int d = 0; d < NB; ++d) {
+        if (d < nb) {   // uniform
+            f32x4_t acc[2], o[2];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                const float bi = i < L ? sB[i] : 0.0f;
+                acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
+                acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
+            }
+            o[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            o[1] = o[0];
+#pragma unroll
+            for (int e = 0; e < d; ++e) {
+                const float4 n4 = tN[tri(d, e)][lane];
+                const float4 m4 = tM[tri(d, e)][lane];
+                const f32x4_t nn = {n4.x, n4.y, n4.z, n4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    acc[c] = mm16(nn, U[e][c], acc[c]);
+                    o[c] = mm16(mm, U[e][c], o[c]);
+                }
+            }
+            const float4 t4 = tT[d][lane];
+            const float4 m4 = tM[tri(d, d)][lane];
+            const f32x4_t tt = {t4.x, t4.y, t4.z, t4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                U[d][c] = mm16(tt, acc[c], f32x4_t{0.f, 0.f, 0.f, 0.f});
+                o[c] = mm16(mm, U[d][c], o[c]);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                if (i < L) {
+                    *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
+                        make_float2(a.scale * o[0][v], a.scale * o[1][v]);
+                    *reinterpret_cast<float2 *>(up + (ru(i) * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                }
+            }
+        }
+    }
+    if (h == 0 && tid == 0)
+        a.st.fill[s] = L;
+}
+
+// ---------------------------------------------------------------------------
+// launch
+// ---------------------------------------------------------------------------
+int launch_direct(int dk, int in_dtype, const DirectArgs &a, int blocks, hipStream_t stream)
+{
+    if (dk == 128 && in_dtype == KVB_BF16) {
+        if (a.st.block_table)
+            launch(kvb_direct_mfma_kernel<true>, blocks, stream, a);
+        else
+            launch(kvb_direct_mfma_kernel<false>, blocks, stream, a);
+        return KVB_OK;
+    }
+    return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_direct_kernel<D, TIn); });
+}
+
+}  // namespace kvb_impl
