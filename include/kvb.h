@@ -48,7 +48,8 @@ extern "C" {
 
 #define KVB_MAX_CAP        128 /* largest `cap` (the paper buffers at most d records, Sec. 3.4) */
 #define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
-#define KVB_MAX_DIRECT_LEN  64 /* largest Lmax of kvb_direct in this build                      */
+#define KVB_MAX_DIRECT_LEN 128 /* largest Lmax of kvb_direct (Sec. 3.4: contexts up to d tokens);
+                                  bf16 inputs with d = 128; the other compiled pairs take 64     */
 #define KVB_MAX_BLOCKS      16 /* longest block-table row (KVB_MAX_CAP / smallest block)        */
 
 /* kvb_store.flags: how the state should travel through the caches.  With neither bit the
@@ -212,7 +213,8 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
  * is discarded).  `state` is neither read nor written.  Decoding then continues
  * with kvb_decode (state NULL), and kvb_flush on a zeroed state folds the
  * records into a state once the context outgrows the buffer.
- *   len   device int32 [B], 0..Lmax        Lmax 1..min(cap, KVB_MAX_DIRECT_LEN)
+ *   len   device int32 [B], 0..Lmax        Lmax 1..min(cap, KVB_MAX_DIRECT_LEN); above 64 only for
+ *         bf16 inputs with d = 128 (KVB_EUNSUPPORTED otherwise)
  *   q, k  device [B, Lmax, Hk, dk]  v device [B, Lmax, Hv, dv]  g, beta device [B, Lmax, Hv]
  *   out   device [B, Lmax, Hv, dv] fp32; rows >= len[b] are not written
  * len[b] outside 0..Lmax is clamped to Lmax with KVB_STATUS_OVERFLOW.

@@ -12,7 +12,7 @@ namespace kvb_impl {
 template <int D, typename TIn, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 {
-    constexpr int LM = KVB_MAX_DIRECT_LEN;
+    constexpr int LM = 64;   // longest context of this kernel
     __shared__ float sK[LM][D + 1];
     __shared__ float sQ[LM][D + 1];
     __shared__ float cK[LM][LM + 1];
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     const DirectArgs a)
 {
     constexpr int D = 128;
-    constexpr int LM = KVB_MAX_DIRECT_LEN;
+    constexpr int LM = 64;   // longest context of this kernel
     constexpr int NB = LM / 16;                 // blocks of 16 rows (4)
     constexpr int NLOW = NB * (NB + 1) / 2;     // lower-triangular block pairs (10)
     constexpr int GS = D + 8;                   // LDS row stride of the staged keys / queries (272 B:
@@ -437,17 +437,331 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 }
 
 // ---------------------------------------------------------------------------
+// kvb_direct for contexts of 65 .. 128 tokens (bf16, d = 128): the same method with 8 blocks of 16
+// rows.  Kept apart from the kernel above, which is tuned around "4 blocks, one per wave" (its raw
+// Gram tiles and query operands all fit in registers at once).  Here a wave owns two diagonal
+// blocks and 16 of the 64 off-diagonal k.k and q.k tiles; the query rows of a tile are fetched
+// one tile ahead; the tile region (80 tiles, 80 KB) again takes the place of the staged keys.
+// ---------------------------------------------------------------------------
+template <bool PAGED>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void kvb_direct_mfma_long_kernel(
+    const DirectArgs a)
+{
+    constexpr int D = 128;
+    constexpr int NB = 8;                       // blocks of 16 rows
+    constexpr int LM = 16 * NB;                 // 128
+    constexpr int NLOW = NB * (NB + 1) / 2;     // block pairs d >= e (36)
+    constexpr int NKK = NB * (NB - 1) / 2;      // off-diagonal k.k pairs (28)
+    constexpr int NTPW = NB * NB / NW;          // off-diagonal k.k + all q.k tiles per wave (16)
+    constexpr int DPW = NB / NW;                // diagonal blocks per wave (2)
+    constexpr int GS = D + 8;
+    constexpr int STAGE_BYTES = LM * GS * 2;
+    constexpr int TILE_BYTES = (NKK + NLOW + NB) * 64 * 16;   // 72 KB: two workgroups per CU
+    __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
+    __shared__ float sG[LM];
+    __shared__ float sB[LM];
+    __shared__ int sBlk[NW][MAX_BLOCKS];
+    bf16_t *sK = reinterpret_cast<bf16_t *>(region);
+    float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
+    float4(*tM)[64] = tN + NKK;
+    float4(*tT)[64] = tM + NLOW;
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int c16 = lane % 16, lq = lane / 16;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int r = a.Hv / a.Hk;
+    const int hk = h / r;
+    const int Lmax = a.Lmax;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    int L = a.len[b];
+    if (L < 0 || L > Lmax) {
+        L = Lmax;
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+    }
+    if (L == 0) {
+        if (h == 0 && tid == 0)
+            a.st.fill[s] = 0;
+        return;
+    }
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
+    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
+    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
+    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const int nb = (L + 15) / 16;
+    auto tri = [](int d, int e) { return d * (d + 1) / 2 + e; };    // slot of pair d >= e
+    auto trn = [](int d, int e) { return d * (d - 1) / 2 + e; };    // slot of pair d > e
+    // tile t of the dealing order -> block pair: t < NKK are the k.k pairs (d > e), row by row,
+    // then the q.k pairs (d >= e), row by row.  Uniform, a handful of scalar steps.
+    auto pair_of = [&](int t, int &d, int &e, bool &isq) {
+        isq = t >= NKK;
+        if (!isq) {
+            d = 1;
+            while (t >= d) {
+                t -= d;
+                ++d;
+            }
+        } else {
+            t -= NKK;
+            d = 0;
+            while (t > d) {
+                t -= d + 1;
+                ++d;
+            }
+        }
+        e = t;
+    };
+
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const int srow = tid / 16, sc8 = tid % 16;
+    const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const bf16_t *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
+    const uint32_t qk_stride = (uint32_t)a.Hk * D, v_stride = (uint32_t)a.Hv * D;
+    const int col2 = 32 * wave + 2 * c16;
+
+    // ---- keys: load, stage, append to the buffer --------------------------------
+    u32x4_t kst[NB];
+#pragma unroll
+    for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
+        const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
+        kst[p] = u32x4_t{0u, 0u, 0u, 0u};
+        if (p < nb)   // uniform
+            kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
+    }
+    // cumulative log decay and beta: wave 0 takes tokens 0..63, wave 1 tokens 64..127 (it adds
+    // the sum of the first 64 decays, which it forms itself)
+    if (wave < 2) {
+        const int t0 = 64 * wave + lane;
+        float gv = t0 < L ? a.g[((size_t)b * Lmax + t0) * a.Hv + h] : 0.0f;
+        const float bv = t0 < L ? a.beta[((size_t)b * Lmax + t0) * a.Hv + h] : 0.0f;
+        float base = 0.0f;
+        if (wave == 1) {
+            base = lane < L ? a.g[((size_t)b * Lmax + lane) * a.Hv + h] : 0.0f;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1)
+                base += __shfl_xor(base, off);
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float t = __shfl_up(gv, off);
+            if (lane >= off)
+                gv += t;
+        }
+        gv += base;
+        sG[t0] = gv;
+        sB[t0] = bv;
+        if (t0 < L)
+            a.st.buf_G[ru(t0)] = gv;
+    }
+    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k);
+#pragma unroll
+    for (int p = 0; p < NB; ++p) {
+        if (p < nb) {   // uniform
+            *reinterpret_cast<u32x4_t *>(sK + (16 * p + srow) * GS + 8 * sc8) = kst[p];
+            if (h % r == 0 && 16 * p + srow < L)
+                *reinterpret_cast<u32x4_t *>(kb + rk(16 * p + srow) * D + 8 * sc8) = kst[p];
+        }
+    }
+    __syncthreads();
+
+    // ---- raw Gram tiles ----------------------------------------------------------
+    f32x4_t gdiag[DPW];
+#pragma unroll
+    for (int x = 0; x < DPW; ++x) {
+        const int d = wave + NW * x;
+        gdiag[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (d < nb)
+            gdiag[x] = gram16<GS>(sK + (16 * d + c16) * GS, sK + (16 * d + c16) * GS, lq);
+    }
+    // query rows of a q.k tile, in the operand layout (row 16 d + c16, k = 8 lq + 32 step),
+    // requested one tile ahead of their use
+    auto load_q = [&](int t, u32x4_t(&qq)[4]) {
+        int d, e;
+        bool isq;
+        pair_of(t, d, e, isq);
+        const uint32_t o = (uint32_t)min(16 * d + c16, L - 1) * qk_stride + 8 * lq;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            qq[st] = u32x4_t{0u, 0u, 0u, 0u};
+            if (isq && d < nb)   // uniform
+                qq[st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
+        }
+    };
+    f32x4_t gsh[NTPW];
+    u32x4_t qa[4], qb[4];
+    load_q(wave, qa);
+#pragma unroll
+    for (int n = 0; n < NTPW; ++n) {
+        const int t = wave + NW * n;
+        if (n + 1 < NTPW) {
+            if (n % 2 == 0)
+                load_q(t + NW, qb);
+            else
+                load_q(t + NW, qa);
+        }
+        int d, e;
+        bool isq;
+        pair_of(t, d, e, isq);
+        gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (d < nb) {   // uniform
+            if (!isq) {
+                gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
+            } else {
+                const bf16_t *arow = sK + (16 * e + c16) * GS;
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
+                    gsh[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, n % 2 == 0 ? qa[st] : qb[st]),
+                        gsh[n], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();   // every wave is done with the staged rows: the region now takes the tiles
+
+    // v in B-form: rows 16 d + 4 lq + v, this lane's two adjacent columns
+    uint32_t v_raw[NB][4];
+#pragma unroll
+    for (int d = 0; d < NB; ++d)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            v_raw[d][v] = 0u;
+            if (d < nb)   // uniform
+                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+        }
+
+    // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
+#pragma unroll
+    for (int n = 0; n < NTPW; ++n) {
+        int d, e;
+        bool isq;
+        pair_of(wave + NW * n, d, e, isq);
+        if (d < nb) {
+            const int i = 16 * d + c16;
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int l = 16 * e + 4 * lq + v;
+                const bool ok = i < L && (isq ? l <= i : l < i);
+                const float w = ok ? fast_exp(sG[i] - sG[l]) : 0.0f;
+                o[v] = (isq ? w : -sB[i] * w) * gsh[n][v];
+            }
+            const float4 o4 = make_float4(o[0], o[1], o[2], o[3]);
+            if (isq)
+                tM[tri(d, e)][lane] = o4;
+            else
+                tN[trn(d, e)][lane] = o4;
+        }
+    }
+    // T_d = (I + N_dd)^-1 for this wave's diagonal blocks (see the kernel above)
+#pragma unroll
+    for (int x = 0; x < DPW; ++x) {
+        const int d = wave + NW * x;
+        if (d < nb) {
+            f32x4_t na, nbm, ia;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ia_i = 16 * d + c16, ia_l = 16 * d + 4 * lq + v;
+                const int ib_i = ia_l, ib_l = ia_i;
+                const float wa = (ia_i < L && ia_l < ia_i) ? sB[ia_i] * fast_exp(sG[ia_i] - sG[ia_l]) : 0.0f;
+                const float wb = (ib_i < L && ib_l < ib_i) ? sB[ib_i] * fast_exp(sG[ib_i] - sG[ib_l]) : 0.0f;
+                na[v] = wa * gdiag[x][v];
+                nbm[v] = wb * gdiag[x][v];
+                ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
+            }
+            const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+            const f32x4_t n2b = mm16(na, nbm, z), n2a = mm16(nbm, na, z);
+            const f32x4_t n4b = mm16(n2a, n2b, z), n4a = mm16(n2b, n2a, z);
+            const f32x4_t n8b = mm16(n4a, n4b, z);
+            f32x4_t p = mm16(ia + n2b, ia - na, z);
+            p = mm16(ia + n4b, p, z);
+            p = mm16(ia + n8b, p, z);
+            tT[d][lane] = make_float4(p[0], p[1], p[2], p[3]);
+        }
+    }
+    __syncthreads();
+
+    // ---- block forward substitution and outputs, this wave's 32 columns ----------
+    f32x4_t U[NB][2];
+    float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
+    float *up = a.st.buf_u;
+#pragma unroll
+    for (int d = 0; d < NB; ++d) {
+        if (d < nb) {   // uniform
+            f32x4_t acc[2], o[2];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                const float bi = i < L ? sB[i] : 0.0f;
+                acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
+                acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
+            }
+            o[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            o[1] = o[0];
+#pragma unroll
+            for (int e = 0; e < d; ++e) {
+                const float4 n4 = tN[trn(d, e)][lane];
+                const float4 m4 = tM[tri(d, e)][lane];
+                const f32x4_t nn = {n4.x, n4.y, n4.z, n4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    acc[c] = mm16(nn, U[e][c], acc[c]);
+                    o[c] = mm16(mm, U[e][c], o[c]);
+                }
+            }
+            const float4 t4 = tT[d][lane];
+            const float4 m4 = tM[tri(d, d)][lane];
+            const f32x4_t tt = {t4.x, t4.y, t4.z, t4.w}, mm = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                U[d][c] = mm16(tt, acc[c], f32x4_t{0.f, 0.f, 0.f, 0.f});
+                o[c] = mm16(mm, U[d][c], o[c]);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * d + 4 * lq + v;
+                if (i < L) {
+                    *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
+                        make_float2(a.scale * o[0][v], a.scale * o[1][v]);
+                    *reinterpret_cast<float2 *>(up + (ru(i) * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                }
+            }
+        }
+    }
+    if (h == 0 && tid == 0)
+        a.st.fill[s] = L;
+}
+
+// ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
 int launch_direct(int dk, int in_dtype, const DirectArgs &a, int blocks, hipStream_t stream)
 {
     if (dk == 128 && in_dtype == KVB_BF16) {
-        if (a.st.block_table)
+        if (a.Lmax > 64) {   // 5 .. 8 blocks of 16 rows
+            if (a.st.block_table)
+                launch(kvb_direct_mfma_long_kernel<true>, blocks, stream, a);
+            else
+                launch(kvb_direct_mfma_long_kernel<false>, blocks, stream, a);
+        } else if (a.st.block_table) {
             launch(kvb_direct_mfma_kernel<true>, blocks, stream, a);
-        else
+        } else {
             launch(kvb_direct_mfma_kernel<false>, blocks, stream, a);
+        }
         return KVB_OK;
     }
+    if (a.Lmax > 64)   // the plain kernel holds a 64-token context in LDS
+        return KVB_EUNSUPPORTED;
     return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_direct_kernel<D, TIn); });
 }
 

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libkvb.so")
 
 OK, EINVAL, EUNSUPPORTED, EHIP = 0, -1, -2, -3
 F32, BF16 = 0, 1
-MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 64
+MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 128
 STATUS_OVERFLOW = 1
 STATUS_BADPATH = 2
 STORE_STREAM, STORE_RESIDENT = 1, 2

@@ -101,7 +101,7 @@ def test_flush_verify_direct_argument_ranges():
     assert kvb.kvb_flush(kvb.shape(**{**GOOD, "B": 0}), _store(state=None), A, A, 1, stream=0, check=False) == kvb.OK
     for T in (0, 9, 17):
         assert kvb.kvb_verify(sh, st, A, T, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
-    for Lmax in (0, 17, 65):
+    for Lmax in (0, 17, 129):
         assert kvb.kvb_direct(sh, st, A, A, Lmax, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
     assert kvb.kvb_direct(sh, st, A, None, 8, A, A, A, A, A, A, stream=0, check=False) == kvb.EINVAL
 

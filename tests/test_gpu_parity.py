@@ -317,7 +317,8 @@ def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode
 
 
 @pytest.mark.parametrize("d, in_dtype, Lmax", [(128, "bf16", 64), (128, "bf16", 7), (32, "f32", 16),
-                                               (64, "bf16", 33), (128, "f32", 20)])
+                                               (64, "bf16", 33), (128, "f32", 20), (128, "bf16", 128),
+                                               (128, "bf16", 65), (128, "bf16", 100)])
 def test_direct_small(d, in_dtype, Lmax):
     e = _direct_case(B=5, Hk=2, Hv=4, d=d, Lmax=Lmax, cap=max(Lmax, 8), in_dtype=in_dtype, seed=50 + Lmax)
     say("direct d=%d %s Lmax=%d rel err out/u/decode/state: %.2e %.2e %.2e %.2e" % ((d, in_dtype, Lmax) + e))
@@ -791,3 +792,22 @@ def test_kv_only_speculative_decoding_commits_without_a_state():
         assert np.array_equal(lay.fill(), pos)
     assert worst < H.TOL["bf16"], worst
     assert not lay.status().any()
+
+
+def test_direct_long_contexts_full_heads_and_paged():
+    """Contexts up to d = 128 tokens (Sec. 3.4) at the model's head counts, ragged lengths that
+    cover every block count, then paged records; each followed by the fold into a zero state."""
+    lens = np.array([128, 127, 113, 112, 97, 96, 81, 80, 65, 64, 33, 1], np.int32)
+    e = _direct_case(B=len(lens), Hk=16, Hv=32, d=128, Lmax=128, cap=128, in_dtype="bf16", seed=720, lens=lens,
+                     then_decode=False)
+    say("direct L<=128 rel err out/u/decode/state: %.2e %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    e = _direct_case(B=4, Hk=1, Hv=2, d=128, Lmax=120, cap=128, in_dtype="bf16", seed=721, block_size=16)
+    assert max(e) < H.TOL["bf16"], e
+
+
+def test_direct_beyond_64_needs_bf16_d128():
+    lay = H.Layer(2, 1, 2, 32, 32, cap=128, in_dtype="f32", with_state=False)
+    z = torch.zeros(1, device="cuda")
+    rc = kvb.kvb_direct(lay.shape(), lay.ds.c(False), lay.slot, lay.slot, 100, z, z, z, z, z, z, check=False)
+    assert rc == kvb.EUNSUPPORTED
