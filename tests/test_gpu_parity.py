@@ -811,3 +811,44 @@ def test_direct_beyond_64_needs_bf16_d128():
     z = torch.zeros(1, device="cuda")
     rc = kvb.kvb_direct(lay.shape(), lay.ds.c(False), lay.slot, lay.slot, 100, z, z, z, z, z, z, check=False)
     assert rc == kvb.EUNSUPPORTED
+
+
+# --------------------------------------------------------------------------- seeded random configurations
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configurations(seed):
+    """Every call at a seeded random shape: head counts and grouping, head size, input type, chunk
+    and capacity (not multiples of anything), drafts, tree shape, contiguous or paged records."""
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.choice([32, 64, 128, 128]))
+    in_dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    Hk = int(rng.integers(1, 4))
+    Hv = Hk * int(rng.integers(1, 4))
+    B = int(rng.integers(1, 6))
+    T = int(rng.integers(1, 9))
+    C = int(rng.integers(1, 41))
+    block = [None, 8, 16, 32][int(rng.integers(0, 4))]
+    tol = H.TOL[in_dtype]
+    tag = "seed %d: d=%d %s Hk=%d Hv=%d B=%d T=%d C=%d block=%s" % (seed, d, in_dtype, Hk, Hv, B, T, C, block)
+    say(tag)
+    # decode + flush over two and a half chunks
+    steps = 2 * C + C // 2 + 1
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 6)
+    tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, in_dtype)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, block_size=block)
+    o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=bool(rng.integers(0, 2)))
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    assert max(e) < tol, (tag, "decode", e)
+    assert lay.spare_clean() and not lay.status().any()
+    # verification (a chain or a tree) on top of a ragged buffer
+    cap = C - 1 + T
+    if bool(rng.integers(0, 2)):
+        e = _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block)
+    else:
+        e = _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block)
+    assert max(e) < tol, (tag, "verify", e)
+    # a short context from the buffer alone
+    Lmax = int(rng.integers(1, 65))
+    e = _direct_case(B, Hk, Hv, d, Lmax, max(Lmax + int(rng.integers(0, 9)), 1), in_dtype, 9200 + seed,
+                     block_size=block)
+    assert max(e) < tol, (tag, "direct", e)
