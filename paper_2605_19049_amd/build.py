@@ -34,7 +34,9 @@ def _clean(text):
 def build_lib(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     extra = os.environ.get("KVB_EXTRA_HIPCC_FLAGS", "").split()
-    work = tempfile.mkdtemp(prefix="kvb_build_")
+    # objects go to a scratch folder inside the package (ignored by git), removed afterwards
+    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
+    work = tempfile.mkdtemp(prefix="obj_", dir=os.path.join(HERE, "_build"))
     try:
         procs = []
         for src in SOURCES:
