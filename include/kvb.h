@@ -34,7 +34,7 @@
 extern "C" {
 #endif
 
-#define KVB_VERSION 100
+#define KVB_VERSION 110 /* 110: kvb_store carries the block-table fields; kvb_verify_tree, kvb_compact */
 
 /* return codes */
 #define KVB_OK            0
