@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_error_strings():
-    assert kvb.version() == 100
+    assert kvb.version() == 110
     assert kvb.strerror(kvb.OK) == "ok"
     assert "invalid" in kvb.strerror(kvb.EINVAL)
     assert "unsupported" in kvb.strerror(kvb.EUNSUPPORTED)
