@@ -92,8 +92,16 @@ def test_qwen3next_decode_full(fused):
     assert fills == [(t + 1) % w.C for t in range(w.steps)]
 
 
+def _scattered(B, seed):
+    """Layer keyword arguments that put the B requests into random slots of a larger store."""
+    n_slots = B + 3
+    slots = np.random.default_rng(seed).permutation(n_slots)[:B].astype(np.int32)
+    return dict(n_slots=n_slots, slots=slots)
+
+
 # --------------------------------------------------------------------------- verify
-def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=False, block_size=None):
+def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=False, block_size=None,
+                 scatter=False):
     rng = np.random.default_rng(seed)
     fill_hi = C - 1 if fill_hi is None else fill_hi
     S0 = np.zeros((B, Hv, d, d), np.float32) if kv_only else H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 16)
@@ -101,7 +109,8 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     wtok = synth.token_stream(rng, B, max(1, fill_hi), Hk, Hv, d, d, in_dtype)
     vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
     acc = synth.accepted_lengths(rng, B, T)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size,
+                  **(_scattered(B, seed) if scatter else {}))
     lay.set_state(S0)
     ragged_warmup(lay, fills, wtok)
     # oracle: true state after the warm-up tokens
@@ -131,7 +140,8 @@ def _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, fill_hi=None, kv_only=
     return e_out, e_u, e_S
 
 
-def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=False, block_size=None):
+def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=False, block_size=None,
+               scatter=False):
     """kvb_verify_tree + kvb_compact + kvb_flush against the oracle run along every root path."""
     rng = np.random.default_rng(seed)
     fill_hi = min(C - 1, cap - T)
@@ -141,7 +151,8 @@ def _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, seed, kind="random", kv_only=F
     vtok = synth.token_stream(rng, B, T, Hk, Hv, d, d, in_dtype)
     parent = synth.draft_trees(rng, B, T, kind)
     leaf, path, plen = synth.accepted_paths(rng, parent)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, block_size=block_size,
+                  **(_scattered(B, seed) if scatter else {}))
     lay.set_state(S0)
     ragged_warmup(lay, fills, wtok)
     _, _, S_true, _ = oracle.gdn_sequence(S0, wtok["q"], wtok["k"], wtok["v"], wtok["g"], wtok["beta"], lens=fills)
@@ -276,12 +287,14 @@ def test_spec_verify_tree_full():
 
 
 # --------------------------------------------------------------------------- direct
-def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True, block_size=None):
+def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True, block_size=None,
+                 scatter=False):
     rng = np.random.default_rng(seed)
     if lens is None:
         lens = synth.context_lengths(rng, B, 1, Lmax)
     tok = synth.token_stream(rng, B, Lmax, Hk, Hv, d, d, in_dtype)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False, block_size=block_size)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False, block_size=block_size,
+                  **(_scattered(B, seed) if scatter else {}))
     lay.ds.fill.fill_(3)          # stale fill must be discarded
     out = torch.full((B, Lmax, Hv, d), float("nan"), dtype=torch.float32, device="cuda")
     lay.direct(H.dev(lens), Lmax, H.upload_tokens(tok, in_dtype), out)
@@ -307,7 +320,7 @@ def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode
         o1_ref, _, S_ref = oracle.gdn_sequence(S_ref, nt["q"], nt["k"], nt["v"], nt["g"], nt["beta"],
                                                lens=(lens < cap).astype(np.int32))[:3]
         e_dec = H.rel_err(o1.cpu().numpy(), o1_ref[room, 0])
-    lay.ds.state = torch.zeros((B, Hv, d, d), dtype=torch.float32, device="cuda")
+    lay.ds.state = torch.zeros((lay.n_slots, Hv, d, d), dtype=torch.float32, device="cuda")
     lay.flush(1)
     torch.cuda.synchronize()
     e_S = H.rel_err(lay.get_state(), S_ref)
@@ -827,6 +840,7 @@ def test_random_configurations(seed):
     T = int(rng.integers(1, 9))
     C = int(rng.integers(1, 41))
     block = [None, 8, 16, 32][int(rng.integers(0, 4))]
+    scatter = bool(rng.integers(0, 2))
     tol = H.TOL[in_dtype]
     tag = "seed %d: d=%d %s Hk=%d Hv=%d B=%d T=%d C=%d block=%s" % (seed, d, in_dtype, Hk, Hv, B, T, C, block)
     say(tag)
@@ -834,7 +848,8 @@ def test_random_configurations(seed):
     steps = 2 * C + C // 2 + 1
     S0 = H.prefix_state(rng, B, Hk, Hv, d, d, in_dtype, 6)
     tok = synth.token_stream(rng, B, steps, Hk, Hv, d, d, in_dtype)
-    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, block_size=block)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype=in_dtype, block_size=block,
+                  **(_scattered(B, seed) if scatter else {}))
     o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=bool(rng.integers(0, 2)))
     o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
     e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
@@ -843,12 +858,12 @@ def test_random_configurations(seed):
     # verification (a chain or a tree) on top of a ragged buffer
     cap = C - 1 + T
     if bool(rng.integers(0, 2)):
-        e = _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block)
+        e = _verify_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block, scatter=scatter)
     else:
-        e = _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block)
+        e = _tree_case(B, Hk, Hv, d, C, cap, T, in_dtype, 9100 + seed, block_size=block, scatter=scatter)
     assert max(e) < tol, (tag, "verify", e)
     # a short context from the buffer alone
     Lmax = int(rng.integers(1, 65))
     e = _direct_case(B, Hk, Hv, d, Lmax, max(Lmax + int(rng.integers(0, 9)), 1), in_dtype, 9200 + seed,
-                     block_size=block)
+                     block_size=block, scatter=scatter)
     assert max(e) < tol, (tag, "direct", e)
