@@ -22,6 +22,8 @@ HIPCC_FLAGS = [
     # keep the single-lane ticket atomics as written: the wave-aggregating rewrite reads
     # the result back at once, which would make the wave wait for its whole state tile
     "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
+    # leading scalar kernel arguments arrive in SGPRs at wave launch (kvb_step_kernel uses it)
+    "-mllvm", "-amdgpu-kernarg-preload-count=4",
     "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

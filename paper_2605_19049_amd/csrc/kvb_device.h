@@ -165,11 +165,12 @@ __device__ __forceinline__ void store_raw8(bf16_t *p, const Raw8<bf16_t> &r)
 // that XCD x works on one contiguous eighth of the (request, head) units: all heads of a
 // request then share an L2, which keeps the per-request ticket atomics and the keys that
 // grouped heads share inside one XCD.
-__device__ __forceinline__ int logical_block()
+__device__ __forceinline__ int logical_block(int n)
 {
-    const int n = gridDim.x, x = blockIdx.x;
+    const int x = blockIdx.x;
     return (n % 8 == 0) ? (x % 8) * (n / 8) + x / 8 : x;
 }
+__device__ __forceinline__ int logical_block() { return logical_block(gridDim.x); }
 
 struct Store {
     float *state;
@@ -298,15 +299,15 @@ extern thread_local kvb_timer *g_armed;
 
 // One kernel launch.  If this thread armed a timer, the launch carries its two events so
 // that they hold the kernel's own begin / end timestamps.
-template <typename Args>
-void launch(void (*kernel)(Args), int blocks, hipStream_t stream, const Args &a)
+template <typename... Params, typename... Args>
+void launch(void (*kernel)(Params...), int blocks, hipStream_t stream, const Args &...a)
 {
     kvb_timer *t = g_armed;
     g_armed = nullptr;
     if (t)
-        hipExtLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, t->start, t->stop, 0, a);
+        hipExtLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, t->start, t->stop, 0, a...);
     else
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, a...);
 }
 
 // Picks the paged or the contiguous instance of a kernel template whose last parameter is PAGED;

@@ -38,8 +38,13 @@ __device__ __forceinline__ float group_sum(float x)
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
 template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
-__global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
+__global__ __launch_bounds__(NT) void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg,
+                                                      const StepArgs a)
 {
+    // The three leading arguments repeat a.slot, a.Hv and the grid size: as plain leading kernel
+    // arguments they are preloaded into scalar registers at wave launch (the build asks for it), so
+    // the load of slot[b] -- the head of the dependent chain to the first state byte -- goes out at
+    // once instead of after the round trip that fetches the argument block.
     constexpr int LPR = D / 4;       // lanes covering one state row with float4
     constexpr int RPP = NT / LPR;    // rows covered by the workgroup per pass
     constexpr int NPASS = D / RPP;   // state rows per thread
@@ -69,15 +74,15 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
     __shared__ __attribute__((aligned(16))) float uu[FUSE ? LT : 1][D];  // u_l tile
 
     const int tid = threadIdx.x;
-    const int lb = logical_block();
-    const int b = lb / a.Hv;
-    const int h = lb % a.Hv;
+    const int lb = logical_block(nblocks_arg);
+    const int b = lb / Hv_arg;
+    const int s = slot_arg[b];
+    __builtin_amdgcn_sched_barrier(0);   // nothing that needs the argument block goes above this load
+    const int h = lb % Hv_arg;
     const int r = a.Hv / a.Hk;
     const int hk = h / r;
     const int T = TM == 1 ? 1 : a.T;
     const int cap = a.cap;
-
-    const int s = a.slot[b];
     if (s < 0 || s >= a.st.n_slots)
         return;
 
@@ -591,6 +596,14 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const StepArgs a)
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
+#define LAUNCH_STEP(blocks, stream, a, ...)                                            \
+    do {                                                                               \
+        if ((a).st.block_table)                                                        \
+            launch(__VA_ARGS__, true>, blocks, stream, (a).slot, (a).Hv, blocks, a);   \
+        else                                                                           \
+            launch(__VA_ARGS__, false>, blocks, stream, (a).slot, (a).Hv, blocks, a);  \
+    } while (0)
+
 template <int D, typename TIn, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
@@ -600,18 +613,18 @@ void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
     if constexpr (TM == 1) {
         if (a.threshold > 0) {
             if (st)
-                LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, true);
+                LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, true);
             else
-                LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, false);
+                LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, false);
             return;
         }
     }
     if (!a.st.state)
-        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, false, false, false);
+        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, false, false, false);
     else if (st)
-        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, true);
+        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, true);
     else
-        LAUNCH_PAGED(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, false);
+        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, false);
 }
 
 template <int D, typename TIn, int TM>
