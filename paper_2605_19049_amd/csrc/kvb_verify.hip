@@ -19,7 +19,9 @@ namespace kvb_impl {
 // lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives C[4*(l/16)+v][l%16].
 // ---------------------------------------------------------------------------
 template <int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
-__global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
+// (register budget of 4 waves per SIMD for the variants that stream the state through a half window)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WREC <= 32 && HAS_STATE ? 4 : 1)))
+void kvb_verify_mfma_kernel(const StepArgs a)
 {
     constexpr int D = 128;
     constexpr int TMX = KVB_MAX_DRAFTS;                       // 8
@@ -73,20 +75,28 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
     // EARLY: the state's address needs the slot only, so its loads go out before the fill is
     // known and before the long scalar prologue; the records follow and are consumed after the
     // state (the decay gamma_i of row i is then applied to the finished sum over state rows).
-    float2 sreg[D / 4];
+    // State row-quads in flight per wave.  EARLY keeps half of the tile in registers and refills a
+    // register pair as soon as its quad has gone through the matrix cores: 32 registers less, which
+    // is what lets a fourth workgroup onto each CU (the kernel is bound by how well its waves hide
+    // each other's waits, not by bytes in flight).
+    constexpr int WIN = EARLY ? 16 : D / 4;
+    float2 sreg[WIN];
+    const float *sp = a.st.state + (HAS_STATE ? unit * D * D + col2 : 0);
+    auto load_quad = [&](int st) {
+        const float2 *p = reinterpret_cast<const float2 *>(sp + (size_t)(4 * st + lq) * D);
+        if constexpr (STREAM) {
+            typedef float v2f __attribute__((ext_vector_type(2)));
+            const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+            return make_float2(t.x, t.y);
+        } else {
+            return *p;
+        }
+    };
     auto issue_state = [&]() {
         __builtin_amdgcn_sched_barrier(0);
-        const float *sp = a.st.state + unit * D * D + col2;
 #pragma unroll
-        for (int st = 0; st < D / 4; ++st) {
-            const float2 *p = reinterpret_cast<const float2 *>(sp + (size_t)(4 * st + lq) * D);
-            if constexpr (STREAM) {
-                typedef float v2f __attribute__((ext_vector_type(2)));
-                const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
-                sreg[st] = make_float2(t.x, t.y);
-            } else {
-                sreg[st] = *p;
-            }
+        for (int st = 0; st < WIN; ++st) {
+            sreg[st] = load_quad(st);
             __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
         }
     };
@@ -236,8 +246,14 @@ __global__ __launch_bounds__(NT) void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
         for (int st = 0; st < D / 4; ++st) {
             const float aw = sW[4 * st + lq][lm];
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].x, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sreg[st].y, acc1, 0, 0, 0);
+            const float2 sv = sreg[st % WIN];
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sv.x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, sv.y, acc1, 0, 0, 0);
+            if (st + WIN < D / 4) {   // the freed registers take the quad WIN further on
+                __builtin_amdgcn_sched_barrier(0);
+                sreg[st % WIN] = load_quad(st + WIN);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
     if constexpr (EARLY) {
