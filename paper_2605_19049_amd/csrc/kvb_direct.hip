@@ -115,7 +115,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 // and M_il = Gamma_il (q_i.k_l) (l <= i) the parallel form (Eq. 13) is
 //     (I + N) U = Diag(beta) V,      O = M U,
 // solved block row by block row:  U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),
-// T_d = (I + N_dd)^-1 = (I - N)(I + N^2)(I + N^4)(I + N^8)   (N_dd is strictly lower, N^16 = 0),
+// T_d = (I + N_dd)^-1 by blocked inversion (unit_lower_inverse16 below; N_dd is strictly lower),
 // O_d = sum_{e<=d} M_de U_e.
 //   * Gram tiles (k.k, q.k over dk = 128, bf16 operands): v_mfma_f32_16x16x32_bf16.
 //   * everything after that has fp32 operands: v_mfma_f32_16x16x4_f32 (exact products).
@@ -136,6 +136,39 @@ __device__ __forceinline__ f32x4_t mm16(const f32x4_t &xa, const f32x4_t &yb, f3
     for (int v = 0; v < 4; ++v)
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[v], yb[v], acc, 0, 0, 0);
     return acc;
+}
+
+// A-form of (I + N)^-1 for a strictly lower triangular 16 x 16 block N given in both forms
+// (ia: the identity, which reads the same in both).  Blocked inversion, exact: with the
+// diagonal blocks of a 2 x 2 block partition already inverted (T), [[A,0],[C,B]]^-1 =
+// T - T C T.  Three levels: 4 x 4 diagonal blocks D0, where (I + D0)^-1 = (I - D0)(I + D0^2)
+// since D0^4 = 0; then the 4 x 4 blocks C1 under them inside each 8 x 8; then the lower left
+// 8 x 8 block C2.  Every intermediate stays of the size of the inverse itself.  (The plain
+// Neumann product (I - N)(I + N^2)(I + N^4)(I + N^8) is also exact in exact arithmetic, but its
+// powers grow like binomial coefficients when the keys of a block are strongly correlated, and
+// the cancellation then costs four digits.)
+__device__ __forceinline__ f32x4_t unit_lower_inverse16(const f32x4_t &na, const f32x4_t &nb, const f32x4_t &ia,
+                                                        int c16, int lq)
+{
+    f32x4_t d0a, d0b, c1a, c2a;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int ai = c16, al = 4 * lq + v;   // A-form: row, column inside the block
+        const int bi = al, bl = ai;            // B-form
+        d0a[v] = ai / 4 == al / 4 ? na[v] : 0.0f;
+        d0b[v] = bi / 4 == bl / 4 ? nb[v] : 0.0f;
+        c1a[v] = (ai / 8 == al / 8 && ai / 4 == al / 4 + 1) ? na[v] : 0.0f;
+        c2a[v] = (ai >= 8 && al < 8) ? na[v] : 0.0f;
+    }
+    const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+    const f32x4_t d2b = mm16(d0a, d0b, z);                 // D0^2
+    const f32x4_t t0a = mm16(ia + d2b, ia - d0a, z);       // (I - D0)(I + D0^2), A-form
+    const f32x4_t t0b = mm16(ia - d0a, ia + d2b, z);       //                     B-form
+    const f32x4_t p1b = mm16(c1a, t0b, z);                 // C1 T0
+    const f32x4_t t1a = t0a - mm16(p1b, t0a, z);           // T0 - T0 C1 T0
+    const f32x4_t t1b = t0b - mm16(t0a, p1b, z);
+    const f32x4_t p2b = mm16(c2a, t1b, z);                 // C2 T1
+    return t1a - mm16(p2b, t1a, z);                        // T1 - T1 C2 T1
 }
 
 // exp for arguments that are differences of cumulative log decays (<= 0, a few tens at
@@ -371,14 +404,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
             nbm[v] = wb * gdiag[v];
             ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
         }
-        const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
-        const f32x4_t n2b = mm16(na, nbm, z), n2a = mm16(nbm, na, z);
-        const f32x4_t n4b = mm16(n2a, n2b, z), n4a = mm16(n2b, n2a, z);
-        const f32x4_t n8b = mm16(n4a, n4b, z);
-        // A-form of (I - N)(I + N^2), then x (I + N^4), then x (I + N^8)
-        f32x4_t p = mm16(ia + n2b, ia - na, z);
-        p = mm16(ia + n4b, p, z);
-        p = mm16(ia + n8b, p, z);
+        const f32x4_t p = unit_lower_inverse16(na, nbm, ia, c16, lq);
         tT[d][lane] = make_float4(p[0], p[1], p[2], p[3]);
     }
     __syncthreads();
@@ -679,13 +705,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 nbm[v] = wb * gdiag[x][v];
                 ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
             }
-            const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
-            const f32x4_t n2b = mm16(na, nbm, z), n2a = mm16(nbm, na, z);
-            const f32x4_t n4b = mm16(n2a, n2b, z), n4a = mm16(n2b, n2a, z);
-            const f32x4_t n8b = mm16(n4a, n4b, z);
-            f32x4_t p = mm16(ia + n2b, ia - na, z);
-            p = mm16(ia + n4b, p, z);
-            p = mm16(ia + n8b, p, z);
+            const f32x4_t p = unit_lower_inverse16(na, nbm, ia, c16, lq);
             tT[d][lane] = make_float4(p[0], p[1], p[2], p[3]);
         }
     }

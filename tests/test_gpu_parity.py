@@ -867,3 +867,53 @@ def test_random_configurations(seed):
     e = _direct_case(B, Hk, Hv, d, Lmax, max(Lmax + int(rng.integers(0, 9)), 1), in_dtype, 9200 + seed,
                      block_size=block, scatter=scatter)
     assert max(e) < tol, (tag, "direct", e)
+
+
+def test_repeated_keys_and_no_decay_stay_within_tolerance():
+    """Every token carries the same key, beta close to 1 and no decay at all: the coefficients
+    Gamma (k_i.k_l) are all 1, the hardest case for the forward substitution and for the block
+    inverse of kvb_direct.  Decode over several chunks, 8 drafts, and a 64-token context."""
+    rng = np.random.default_rng(170)
+    B, Hk, Hv, d, C = 3, 1, 2, 128, 16
+    def same_key_tokens(T):
+        tok = synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16")
+        tok["k"][:] = tok["k"][:, :1]
+        tok["g"][:] = 0.0
+        tok["beta"][:] = 0.96875          # exactly representable
+        return tok
+    tok = same_key_tokens(40)
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, "bf16", 8)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+    o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=True)
+    o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
+    say("same key, decode rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    # drafts
+    vt = same_key_tokens(8)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=8, in_dtype="bf16")
+    lay.set_state(S0)
+    out = torch.empty((B, 8, Hv, d), dtype=torch.float32, device="cuda")
+    lay.verify(8, H.upload_tokens(vt, "bf16"), out)
+    o_ref, _, _ = oracle.kvb_verify_expected(S0, vt["q"], vt["k"], vt["v"], vt["g"], vt["beta"], np.zeros(B, np.int32))
+    e = H.rel_err(out.cpu().numpy(), o_ref)
+    say("same key, verify rel err: %.2e" % e)
+    assert e < H.TOL["bf16"]
+    # a whole context
+    dt_ = same_key_tokens(64)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=64, in_dtype="bf16", with_state=False)
+    out = torch.empty((B, 64, Hv, d), dtype=torch.float32, device="cuda")
+    lay.direct(H.dev(np.full(B, 64, np.int32)), 64, H.upload_tokens(dt_, "bf16"), out)
+    o_ref, _, _ = oracle.kvb_direct_expected(dt_["q"], dt_["k"], dt_["v"], dt_["g"], dt_["beta"], np.full(B, 64, np.int32))
+    e = H.rel_err(out.cpu().numpy(), o_ref)
+    say("same key, direct rel err: %.2e" % e)
+    assert e < H.TOL["bf16"]
+    # ... and one of 128 tokens (the 8-block kernel)
+    dt_ = same_key_tokens(128)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=128, in_dtype="bf16", with_state=False)
+    out = torch.empty((B, 128, Hv, d), dtype=torch.float32, device="cuda")
+    lay.direct(H.dev(np.full(B, 128, np.int32)), 128, H.upload_tokens(dt_, "bf16"), out)
+    o_ref, _, _ = oracle.kvb_direct_expected(dt_["q"], dt_["k"], dt_["v"], dt_["g"], dt_["beta"], np.full(B, 128, np.int32))
+    e = H.rel_err(out.cpu().numpy(), o_ref)
+    say("same key, direct (128 tokens) rel err: %.2e" % e)
+    assert e < H.TOL["bf16"]
