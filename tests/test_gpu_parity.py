@@ -869,15 +869,28 @@ def test_random_configurations(seed):
     assert max(e) < tol, (tag, "direct", e)
 
 
-def test_repeated_keys_and_no_decay_stay_within_tolerance():
-    """Every token carries the same key, beta close to 1 and no decay at all: the coefficients
-    Gamma (k_i.k_l) are all 1, the hardest case for the forward substitution and for the block
-    inverse of kvb_direct.  Decode over several chunks, 8 drafts, and a 64-token context."""
+@pytest.mark.parametrize("pattern", ["same", "alternating", "anticorrelated"])
+def test_repeated_keys_and_no_decay_stay_within_tolerance(pattern):
+    """Strongly correlated keys, beta close to 1 and no decay at all: the coefficients
+    Gamma (k_i.k_l) are all +-1 (one key; one key with alternating sign) or +-0.9 (two keys with
+    k1.k2 = -0.9 taking turns), the hardest cases for the forward substitution and for the block
+    inverse of kvb_direct.  Decode over several chunks, 8 drafts, contexts of 64 and 128 tokens."""
     rng = np.random.default_rng(170)
     B, Hk, Hv, d, C = 3, 1, 2, 128, 16
     def same_key_tokens(T):
         tok = synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16")
-        tok["k"][:] = tok["k"][:, :1]
+        k1 = tok["k"][:, :1].copy()
+        if pattern == "same":
+            tok["k"][:] = k1
+        elif pattern == "alternating":
+            tok["k"][:] = k1 * ((-1.0) ** np.arange(T))[None, :, None, None]
+        else:
+            r = tok["k"][:, 1:2]
+            r = r - (r * k1).sum(-1, keepdims=True) * k1 / (k1 * k1).sum(-1, keepdims=True)
+            k2 = -0.9 * k1 + np.sqrt(1.0 - 0.81) * r / np.linalg.norm(r, axis=-1, keepdims=True)
+            k2 = synth.round_to_bf16(k2.astype(np.float32)).astype(tok["k"].dtype)
+            for t in range(T):
+                tok["k"][:, t:t + 1] = k1 if t % 2 == 0 else k2
         tok["g"][:] = 0.0
         tok["beta"][:] = 0.96875          # exactly representable
         return tok
@@ -887,7 +900,7 @@ def test_repeated_keys_and_no_decay_stay_within_tolerance():
     o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=True)
     o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
     e = (H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref))
-    say("same key, decode rel err out/u/state: %.2e %.2e %.2e" % e)
+    say(pattern + " key, decode rel err out/u/state: %.2e %.2e %.2e" % e)
     assert max(e) < H.TOL["bf16"]
     # drafts
     vt = same_key_tokens(8)
@@ -897,7 +910,7 @@ def test_repeated_keys_and_no_decay_stay_within_tolerance():
     lay.verify(8, H.upload_tokens(vt, "bf16"), out)
     o_ref, _, _ = oracle.kvb_verify_expected(S0, vt["q"], vt["k"], vt["v"], vt["g"], vt["beta"], np.zeros(B, np.int32))
     e = H.rel_err(out.cpu().numpy(), o_ref)
-    say("same key, verify rel err: %.2e" % e)
+    say(pattern + " key, verify rel err: %.2e" % e)
     assert e < H.TOL["bf16"]
     # a whole context
     dt_ = same_key_tokens(64)
@@ -906,7 +919,7 @@ def test_repeated_keys_and_no_decay_stay_within_tolerance():
     lay.direct(H.dev(np.full(B, 64, np.int32)), 64, H.upload_tokens(dt_, "bf16"), out)
     o_ref, _, _ = oracle.kvb_direct_expected(dt_["q"], dt_["k"], dt_["v"], dt_["g"], dt_["beta"], np.full(B, 64, np.int32))
     e = H.rel_err(out.cpu().numpy(), o_ref)
-    say("same key, direct rel err: %.2e" % e)
+    say(pattern + " key, direct rel err: %.2e" % e)
     assert e < H.TOL["bf16"]
     # ... and one of 128 tokens (the 8-block kernel)
     dt_ = same_key_tokens(128)
@@ -915,5 +928,5 @@ def test_repeated_keys_and_no_decay_stay_within_tolerance():
     lay.direct(H.dev(np.full(B, 128, np.int32)), 128, H.upload_tokens(dt_, "bf16"), out)
     o_ref, _, _ = oracle.kvb_direct_expected(dt_["q"], dt_["k"], dt_["v"], dt_["g"], dt_["beta"], np.full(B, 128, np.int32))
     e = H.rel_err(out.cpu().numpy(), o_ref)
-    say("same key, direct (128 tokens) rel err: %.2e" % e)
+    say(pattern + " key, direct (128 tokens) rel err: %.2e" % e)
     assert e < H.TOL["bf16"]
