@@ -139,8 +139,8 @@ class DecodeJob:
 
 
 def time_other_paths(torch, kvb, synth, traffic, reps=20):
-    """Kernel-level timings of kvb_verify, kvb_direct and a 64-record kvb_flush at the
-    sizes of the spec_verify / short_direct / long_mixed workloads (context numbers only)."""
+    """Kernel-level timings of kvb_verify, kvb_verify_tree, kvb_direct and kvb_flush at the sizes
+    of the spec_verify / short_direct / qwen3next_decode workloads (context numbers only)."""
     import numpy as np
     res = {}
 
@@ -209,6 +209,37 @@ def time_other_paths(torch, kvb, synth, traffic, reps=20):
                          "algorithmic_GBps": byt / sec / 1e9, "TFLOPs": flop / sec / 1e12,
                          "context_tokens_per_s": float(lens.sum()) / sec}
     del ds
+
+    # flush as a launch of its own: every request of the layer at fill m, all of them folded.
+    # The call empties the buffers, so the fill is set again before each launch and the launch
+    # is timed by the library's own kernel timer.
+    def flush_case(B, cap, m):
+        w = synth.WORKLOADS["qwen3next_decode"]
+        ds = kvb.DeviceStore(B, w.Hk, w.Hv, w.dk, w.dv, cap, kvb.BF16)
+        ds.state.normal_(0, 0.5)
+        ds.buf_u.normal_(0, 1.0)
+        ds.buf_k.copy_(torch.nn.functional.normalize(torch.randn_like(ds.buf_k, dtype=torch.float32), dim=-1))
+        ds.buf_G.copy_(-0.25 * torch.arange(1, cap + 1, device="cuda").float().expand_as(ds.buf_G))
+        sh = kvb.shape(B, w.Hk, w.Hv, w.dk, w.dv, cap, kvb.BF16)
+        st = ds.c()
+        slot = torch.arange(B, dtype=torch.int32, device="cuda")
+        call = kvb.bind("kvb_flush", sh, st, slot, None, 1, torch.cuda.current_stream().cuda_stream)
+        tm = kvb.Timer()
+        us = []
+        for _ in range(reps + 4):
+            ds.fill.fill_(m)
+            tm.arm()
+            call()
+            us.append(tm.us())
+        tm.close()
+        us = sorted(us[4:])
+        sec = us[len(us) // 2] * 1e-6
+        byt = traffic.total(traffic.flush_rw(traffic.KVB, m)) * B * w.Hv
+        return {"workload": "qwen3next layer, B=%d, every request at fill %d (cap %d)" % (B, m, cap), "us": sec * 1e6,
+                "algorithmic_GBps": byt / sec / 1e9, "TFLOPs": 2.0 * m * w.dk * w.dv * B * w.Hv / sec / 1e12}
+
+    res["kvb_flush"] = flush_case(64, 16, 16)
+    res["kvb_flush_64_records"] = flush_case(128, 64, 64)
     return res
 
 

@@ -1,4 +1,4 @@
-// kvb_flush_kernel (the deferred state update as its own launch) and kvb_compact_kernel.
+// kvb_flush_kernel and kvb_flush_mfma_kernel (the deferred state update as its own launch), kvb_compact_kernel.
 #include "kvb_device.h"
 
 namespace kvb_impl {
@@ -119,6 +119,212 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// kvb_flush for bf16 keys and d = 128, on the matrix cores.
+//
+// The rank-m update is the dense contraction K^T (Diag(Gamma) U), dk x m by m x dv.  The keys
+// are bf16 as stored, so they are exact operands of v_mfma_f32_16x16x32_bf16; the other factor
+// x = Gamma_l u_l is fp32 and is cut into three bf16 pieces x = x1 + x2 + x3 (8 significand
+// bits each, by masking and exact subtraction), so that k * x = k*x1 + k*x2 + k*x3 holds
+// exactly and the sum is accumulated in fp32 as before.  The bf16 instruction runs at 16 times
+// the rate of the fp32 matrix instruction, so the three products still come at about 5 times
+// that rate and 10 times the rate of plain vector-ALU FMAs, which is what bounds the
+// vector-ALU kernel above from 16 records on.
+//
+// Operand layout (lane = 16 lq + lm): A holds A[lm][8 lq + j], B holds B[8 lq + j][lm],
+// j = 0..7, the result D[4 lq + v][lm], v = 0..3.  The contraction index is the record,
+// 32 records per instruction.  Which state row a tile row stands for, and which column a tile
+// column, is free, and chosen so that every global access is a whole row segment:
+//   tile row mi of row tile rt    = state row 8 mi + rt: one 16-byte load of k_l[8 lm .. 8 lm + 7]
+//                                   holds the lane's element of all 8 row tiles of record l;
+//   tile column ni of column tile t = column 32 wave + 2 ni + t: u and the state are accessed
+//                                   as float2, 16 lanes to a 128-byte line.
+// A lane ends up with rows 32 lq .. 32 lq + 31 of its column pair.  A wave owns 32 columns of
+// all rows and needs nothing from the other waves: the kernel has no barrier.
+// MULTI: more than one 32-record chunk (cap > 32); the sums then stay in registers across the
+// chunks, otherwise each row tile is finished and stored as soon as its six products are done.
+// ---------------------------------------------------------------------------
+template <bool MULTI, bool PAGED>
+// (register budgets: 3 workgroups per CU, 2 where the sums persist)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MULTI ? 2 : 3)))
+void kvb_flush_mfma_kernel(const FlushArgs a)
+{
+    constexpr int D = 128;
+    constexpr int CH = 32;   // records per chunk
+    __shared__ int sBlk[NW][MAX_BLOCKS];
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int lm = lane % 16, lq = lane / 16;
+    const int lb = logical_block();
+    const int b = lb / a.Hv;
+    const int h = lb % a.Hv;
+    const int hk = h / (a.Hv / a.Hk);
+    const int cap = a.cap;
+
+    const int s = a.slot[b];
+    if (s < 0 || s >= a.st.n_slots)
+        return;
+    const int f = a.st.fill[s] & FILL_MASK;
+    int nacc = a.accepted ? a.accepted[b] : 0;
+    if (nacc < 0)
+        nacc = 0;
+    int m = f + nacc;
+    if (m > cap) {
+        m = cap;
+        if (tid == 0 && a.st.status)
+            atomicOr(&a.st.status[s], KVB_STATUS_OVERFLOW);
+    }
+    const bool do_flush = a.st.state != nullptr && m >= a.threshold && m > 0;
+    if (!do_flush) {
+        if (m != f && tid == 0)
+            publish_fill(&a.st.fill[s], a.Hv, m);
+        return;
+    }
+    const size_t unit = (size_t)s * a.Hv + h;
+    const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
+    auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
+    auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
+    const float *Gbuf = a.st.buf_G;
+    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k);
+    const float *ub = a.st.buf_u;
+    const float Glast = Gbuf[ru(m - 1)];
+    const int col2 = 32 * wave + 2 * lm;
+
+    // records 32 c + 8 lq + j of chunk c as raw bits; an index past m is clamped to record 0
+    // (finite values that meet a zero weight)
+    uint4 kraw[8];
+    float2 uraw[8];
+    float Graw[8];
+    auto load_chunk = [&](int c) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int l = CH * c + 8 * lq + j;
+            const int lc = l < m ? l : 0;
+            kraw[j] = *reinterpret_cast<const uint4 *>(kb + rk(lc) * D + 8 * lm);
+            uraw[j] = *reinterpret_cast<const float2 *>(ub + ru(lc) * D + col2);
+            Graw[j] = Gbuf[ru(lc)];
+        }
+    };
+    // first chunk, then the state tile: loads retire in issue order, and the products of the
+    // first chunk run while the state is in flight
+    load_chunk(0);
+    __builtin_amdgcn_sched_barrier(0);
+    // State row tiles in flight: a window of 4 of the 8, refilled tile by tile as the results are
+    // stored (all 8 in flight measured the same and cost a workgroup per CU).
+    constexpr int WIN = 4;
+    float *sp = a.st.state + unit * D * D + col2;
+    float2 sreg[WIN][4];
+    auto issue_state = [&](int rt) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            sreg[rt % WIN][v] = *reinterpret_cast<const float2 *>(sp + (size_t)(32 * lq + 8 * v + rt) * D);
+        __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
+    };
+#pragma unroll
+    for (int rt = 0; rt < WIN; ++rt)
+        issue_state(rt);
+    int ticket = 0;
+    if (tid == 0)
+        ticket = take_ticket(&a.st.fill[s]);
+
+    // B operands of a chunk: piece p of Gamma_l u_l[col2 + t], 8 records to a lane
+    bf16x8_t bop[2][3];
+    auto build_b = [&](int c) {
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            w[j] = CH * c + 8 * lq + j < m ? expf(Glast - Graw[j]) : 0.0f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                r[j] = w[j] * (t ? uraw[j].y : uraw[j].x);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                // the leading 8 significand bits of what is left; the rest is exact in fp32
+                uint32_t top[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    top[j] = __builtin_bit_cast(uint32_t, r[j]) & 0xFFFF0000u;
+                    r[j] -= __builtin_bit_cast(float, top[j]);
+                }
+                uint4 w4;
+                w4.x = (top[0] >> 16) | top[1];
+                w4.y = (top[2] >> 16) | top[3];
+                w4.z = (top[4] >> 16) | top[5];
+                w4.w = (top[6] >> 16) | top[7];
+                bop[t][p] = __builtin_bit_cast(bf16x8_t, w4);
+            }
+        }
+    };
+    // A operand of row tile rt: element rt of each record's 8-element slice
+    auto build_a = [&](int rt) {
+        uint32_t d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = rt / 2 == 0 ? kraw[j].x : rt / 2 == 1 ? kraw[j].y : rt / 2 == 2 ? kraw[j].z : kraw[j].w;
+            d[j] = rt % 2 ? (w >> 16) : (w & 0xFFFFu);
+        }
+        uint4 w4;
+        w4.x = d[0] | (d[1] << 16);
+        w4.y = d[2] | (d[3] << 16);
+        w4.z = d[4] | (d[5] << 16);
+        w4.w = d[6] | (d[7] << 16);
+        return __builtin_bit_cast(bf16x8_t, w4);
+    };
+    auto products = [&](int rt, f32x4_t &c0, f32x4_t &c1) {
+        const bf16x8_t aop = build_a(rt);
+#pragma unroll
+        for (int p = 2; p >= 0; --p) {   // smallest pieces first
+            c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[0][p], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[1][p], c1, 0, 0, 0);
+        }
+    };
+    const float gam = expf(Glast);
+    auto finish = [&](int rt, const f32x4_t &c0, const f32x4_t &c1) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float2 o;
+            o.x = fmaf(gam, sreg[rt % WIN][v].x, c0[v]);
+            o.y = fmaf(gam, sreg[rt % WIN][v].y, c1[v]);
+            *reinterpret_cast<float2 *>(sp + (size_t)(32 * lq + 8 * v + rt) * D) = o;
+        }
+        if (rt + WIN < 8) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue_state(rt + WIN);
+        }
+    };
+    if constexpr (!MULTI) {
+        build_b(0);
+#pragma unroll
+        for (int rt = 0; rt < 8; ++rt) {
+            f32x4_t c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+            products(rt, c0, c1);
+            finish(rt, c0, c1);
+        }
+    } else {
+        f32x4_t acc[8][2];
+#pragma unroll
+        for (int rt = 0; rt < 8; ++rt)
+            acc[rt][0] = acc[rt][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        const int nchunk = (m + CH - 1) / CH;
+        for (int c = 0; c < nchunk; ++c) {
+            if (c > 0)
+                load_chunk(c);
+            build_b(c);
+#pragma unroll
+            for (int rt = 0; rt < 8; ++rt)
+                products(rt, acc[rt][0], acc[rt][1]);
+        }
+#pragma unroll
+        for (int rt = 0; rt < 8; ++rt)
+            finish(rt, acc[rt][0], acc[rt][1]);
+    }
+    if (tid == 0)
+        publish_if_last(&a.st.fill[s], ticket, a.Hv, 0);
+}
+
+// ---------------------------------------------------------------------------
 // kvb_compact: after kvb_verify_tree, the records of the accepted root path
 // (nodes path[0] < path[1] < ...) move from positions f + path[j] to f + j, so that
 // the accepted drafts are a prefix of the T new records and kvb_flush(accepted)
@@ -177,6 +383,13 @@ __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
 // ---------------------------------------------------------------------------
 int launch_flush(int dk, int in_dtype, const FlushArgs &a, int blocks, hipStream_t stream)
 {
+    if (dk == 128 && in_dtype == KVB_BF16) {   // the matrix-core kernel
+        if (a.cap <= 32)
+            LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<false);
+        else
+            LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<true);
+        return KVB_OK;
+    }
     return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_flush_kernel<D, TIn); });
 }
 
