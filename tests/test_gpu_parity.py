@@ -482,6 +482,39 @@ def test_strong_decay_neither_overflows_nor_underflows_to_nan():
     assert max(H.rel_err(o, o_ref), H.rel_err(S, S_ref)) < H.TOL["bf16"]
 
 
+@pytest.mark.parametrize("cap", [16, 64])
+def test_flush_products_keep_fp32_accuracy_over_a_wide_range(cap):
+    """kvb_flush (bf16, d = 128) multiplies bf16 keys with a three-way bf16 split of the fp32
+    factor; the split has to be exact whatever the magnitude.  One record per request on a zero
+    state, v scaled by 1e-30 .. 1e30: every element of S = k^T u must match the oracle to fp32
+    rounding of u and of the product (a dropped third piece would show as 1.5e-5)."""
+    rng = np.random.default_rng(171)
+    scales = np.array([1e-30, 1e-15, 1.0, 1e15, 1e30])
+    B, Hk, Hv, d = len(scales), 1, 2, 128
+    tok = synth.token_stream(rng, B, 1, Hk, Hv, d, d, "bf16")
+    tok["v"] = synth.round_to_bf16((tok["v"] * scales[:, None, None, None]).astype(np.float32))
+    tok["g"][:] = -0.125
+    S0 = np.zeros((B, Hv, d, d), np.float32)
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype="bf16")
+    _, _, S, _ = H.run_decode(lay, S0, tok, cap, final_flush=True)
+    _, _, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    assert np.isfinite(S).all()
+    nz = np.abs(S_ref) > 0
+    rel = np.abs(S - S_ref)[nz] / np.abs(S_ref)[nz]
+    say("flush, one record, scales 1e-30..1e30: max elementwise rel err %.2e" % rel.max())
+    assert rel.max() < 4e-7
+    # several records of mixed magnitude per request: the usual bound, per request
+    tok = synth.token_stream(rng, B, cap, Hk, Hv, d, d, "bf16")
+    mags = 10.0 ** rng.uniform(-3, 3, size=(B, cap))
+    tok["v"] = synth.round_to_bf16((tok["v"] * mags[:, :, None, None]).astype(np.float32))
+    lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype="bf16")
+    _, _, S, _ = H.run_decode(lay, S0, tok, cap, final_flush=True)
+    _, _, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    e = max(H.rel_err(S[b], S_ref[b]) for b in range(B))
+    say("flush, %d records of mixed magnitude: rel err %.2e" % (cap, e))
+    assert e < H.TOL["bf16"]
+
+
 def test_accepting_nothing_appends_nothing():
     rng = np.random.default_rng(74)
     lay = _small_layer(cap=8)
