@@ -1,0 +1,65 @@
+"""Why the delta-value records are fp32: chunkwise decoding emulated in fp64 on the CPU with the
+buffered u rounded to fp32, fp16 or bf16 when it is stored (everything else exact), against the
+token-by-token recurrence of the oracle (App. A.1 Eq. 11-12 vs. Eq. 16).  A rounded u is read by
+the following steps and folded into the state at the next update, so its error stays.  On the
+decode workload's distributions 16-bit records miss the 2e-3 bound that the bf16-input
+configurations are held to; fp32 records are invisible at that level.  (The paper's own
+implementation keeps fp16 records; its accuracy target is not stated.)"""
+import numpy as np
+import pytest
+
+from oracle import gdn
+from paper_2605_19049_amd import synth
+
+
+def _stored(u, kind):
+    if kind == "f32":
+        return u.astype(np.float32).astype(np.float64)
+    if kind == "f16":
+        return u.astype(np.float16).astype(np.float64)
+    return synth.round_to_bf16(u.astype(np.float32)).astype(np.float64)
+
+
+def _chunkwise_one_head(q, k, v, g, beta, C, kind):
+    """Eq. 16 for one (request, head) from a zero state: q, k, v [T, d]; g, beta [T]."""
+    T, d = q.shape
+    S = np.zeros((d, d))
+    ks, us, Gs = [], [], []
+    out = np.zeros((T, d))
+    for t in range(T):
+        G = (Gs[-1] if Gs else 0.0) + g[t]
+        acc = np.exp(G) * (k[t] @ S)
+        ao = np.exp(G) * (q[t] @ S)
+        for kl, ul, Gl in zip(ks, us, Gs):
+            w = np.exp(G - Gl)
+            acc += w * (k[t] @ kl) * ul
+            ao += w * (q[t] @ kl) * ul
+        u = beta[t] * (v[t] - acc)
+        out[t] = ao + (q[t] @ k[t]) * u
+        ks.append(k[t]); us.append(_stored(u, kind)); Gs.append(G)
+        if len(ks) == C:
+            S = np.exp(G) * S
+            for kl, ul, Gl in zip(ks, us, Gs):
+                S += np.exp(G - Gl) * np.outer(kl, ul)
+            ks, us, Gs = [], [], []
+    return out
+
+
+@pytest.mark.parametrize("kind, lo, hi", [("f32", 0.0, 1e-6), ("f16", 2e-3, 1e-2), ("bf16", 1e-2, 1e-1)])
+def test_error_of_rounded_u_records(kind, lo, hi):
+    rng = np.random.default_rng(2)
+    B, Hk, Hv, d, T, C = 4, 2, 4, 128, 256, 16
+    tok = synth.token_stream(rng, B, T, Hk, Hv, d, d, "bf16")
+    S0 = np.zeros((B, Hv, d, d))
+    o_ref, _, _ = gdn.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+    rms = np.sqrt((o_ref ** 2).mean())
+    worst = 0.0
+    for b in range(B):
+        for h in range(Hv):
+            f = lambda x: x.astype(np.float64)
+            o = _chunkwise_one_head(f(tok["q"][b, :, h // (Hv // Hk)]), f(tok["k"][b, :, h // (Hv // Hk)]),
+                                    f(tok["v"][b, :, h]), f(tok["g"][b, :, h]), f(tok["beta"][b, :, h]), C, kind)
+            worst = max(worst, np.abs(o - o_ref[b, :, h]).max())
+    err = worst / rms
+    print("u records %s: max abs err / rms = %.2e" % (kind, err))
+    assert lo <= err <= hi
