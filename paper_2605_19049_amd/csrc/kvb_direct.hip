@@ -219,15 +219,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     constexpr int STAGE_BYTES = LM * GS * 2;
     constexpr int TILE_BYTES = (2 * NLOW + NB) * 64 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
-    __shared__ float sG[LM];
-    __shared__ float sB[LM];
+    __shared__ __attribute__((aligned(16))) float sG[LM];
+    __shared__ __attribute__((aligned(16))) float sB[LM];
     __shared__ int sBlk[NW][MAX_BLOCKS];
     bf16_t *sK = reinterpret_cast<bf16_t *>(region);
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NLOW;
     float4(*tT)[64] = tM + NLOW;
 
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    // (the wave index as a scalar: conditions and tile numbers derived from it are then uniform for
+    // the compiler, scalar branches instead of masked ones)
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
     const int c16 = lane % 16, lq = lane / 16;
     const int lb = logical_block();
     const int b = lb / a.Hv;
@@ -374,13 +376,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
         if (d < nb) {
             const int i = 16 * d + c16;
             const bool isq = t >= 6;
+            // (LDS reads without a condition, then selects: a read under a condition becomes a
+            // branch with a wait of its own, one round trip per element)
+            const float gi = sG[i];
+            const float si = isq ? 1.0f : -sB[i];
+            const float4 gl4 = *reinterpret_cast<const float4 *>(&sG[16 * e + 4 * lq]);
+            const float gl[4] = {gl4.x, gl4.y, gl4.z, gl4.w};
             float o[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int l = 16 * e + 4 * lq + v;
                 const bool ok = i < L && (isq ? l <= i : l < i);
-                const float w = ok ? fast_exp(sG[i] - sG[l]) : 0.0f;
-                o[v] = (isq ? w : -sB[i] * w) * gsh[n][v];
+                o[v] = ok ? si * fast_exp(gi - gl[v]) * gsh[n][v] : 0.0f;
             }
             const float4 o4 = make_float4(o[0], o[1], o[2], o[3]);
             if (isq)
@@ -394,14 +401,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     if (wave < nb) {
         const int d = wave;
         f32x4_t na, nbm, ia;   // N in both forms; identity mask (the same in both forms)
+        const float gc = sG[16 * d + c16], bc = sB[16 * d + c16];
+        const float4 gq4 = *reinterpret_cast<const float4 *>(&sG[16 * d + 4 * lq]);
+        const float4 bq4 = *reinterpret_cast<const float4 *>(&sB[16 * d + 4 * lq]);
+        const float gq[4] = {gq4.x, gq4.y, gq4.z, gq4.w}, bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int ia_i = 16 * d + c16, ia_l = 16 * d + 4 * lq + v;    // A-form indices
             const int ib_i = ia_l, ib_l = ia_i;                            // B-form indices
-            const float wa = (ia_i < L && ia_l < ia_i) ? sB[ia_i] * fast_exp(sG[ia_i] - sG[ia_l]) : 0.0f;
-            const float wb = (ib_i < L && ib_l < ib_i) ? sB[ib_i] * fast_exp(sG[ib_i] - sG[ib_l]) : 0.0f;
-            na[v] = wa * gdiag[v];
-            nbm[v] = wb * gdiag[v];
+            na[v] = (ia_i < L && ia_l < ia_i) ? bc * fast_exp(gc - gq[v]) * gdiag[v] : 0.0f;
+            nbm[v] = (ib_i < L && ib_l < ib_i) ? bq[v] * fast_exp(gq[v] - gc) * gdiag[v] : 0.0f;
             ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
         }
         const f32x4_t p = unit_lower_inverse16(na, nbm, ia, c16, lq);
@@ -422,7 +431,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
-                const float bi = i < L ? sB[i] : 0.0f;
+                const float bi = sB[i];   // zero beyond the context
                 acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
                 acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
             }
@@ -484,15 +493,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     constexpr int STAGE_BYTES = LM * GS * 2;
     constexpr int TILE_BYTES = (NKK + NLOW + NB) * 64 * 16;   // 72 KB: two workgroups per CU
     __shared__ __attribute__((aligned(16))) unsigned char region[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
-    __shared__ float sG[LM];
-    __shared__ float sB[LM];
+    __shared__ __attribute__((aligned(16))) float sG[LM];
+    __shared__ __attribute__((aligned(16))) float sB[LM];
     __shared__ int sBlk[NW][MAX_BLOCKS];
     bf16_t *sK = reinterpret_cast<bf16_t *>(region);
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NKK;
     float4(*tT)[64] = tM + NLOW;
 
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    // (the wave index as a scalar: conditions and tile numbers derived from it are then uniform for
+    // the compiler, scalar branches instead of masked ones)
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
     const int c16 = lane % 16, lq = lane / 16;
     const int lb = logical_block();
     const int b = lb / a.Hv;
@@ -674,13 +685,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         pair_of(wave + NW * n, d, e, isq);
         if (d < nb) {
             const int i = 16 * d + c16;
+            // (LDS reads without a condition, then selects: a read under a condition becomes a
+            // branch with a wait of its own, one round trip per element)
+            const float gi = sG[i];
+            const float si = isq ? 1.0f : -sB[i];
+            const float4 gl4 = *reinterpret_cast<const float4 *>(&sG[16 * e + 4 * lq]);
+            const float gl[4] = {gl4.x, gl4.y, gl4.z, gl4.w};
             float o[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int l = 16 * e + 4 * lq + v;
                 const bool ok = i < L && (isq ? l <= i : l < i);
-                const float w = ok ? fast_exp(sG[i] - sG[l]) : 0.0f;
-                o[v] = (isq ? w : -sB[i] * w) * gsh[n][v];
+                o[v] = ok ? si * fast_exp(gi - gl[v]) * gsh[n][v] : 0.0f;
             }
             const float4 o4 = make_float4(o[0], o[1], o[2], o[3]);
             if (isq)
@@ -695,14 +711,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         const int d = wave + NW * x;
         if (d < nb) {
             f32x4_t na, nbm, ia;
+            const float gc = sG[16 * d + c16], bc = sB[16 * d + c16];
+            const float4 gq4 = *reinterpret_cast<const float4 *>(&sG[16 * d + 4 * lq]);
+            const float4 bq4 = *reinterpret_cast<const float4 *>(&sB[16 * d + 4 * lq]);
+            const float gq[4] = {gq4.x, gq4.y, gq4.z, gq4.w}, bq[4] = {bq4.x, bq4.y, bq4.z, bq4.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int ia_i = 16 * d + c16, ia_l = 16 * d + 4 * lq + v;
                 const int ib_i = ia_l, ib_l = ia_i;
-                const float wa = (ia_i < L && ia_l < ia_i) ? sB[ia_i] * fast_exp(sG[ia_i] - sG[ia_l]) : 0.0f;
-                const float wb = (ib_i < L && ib_l < ib_i) ? sB[ib_i] * fast_exp(sG[ib_i] - sG[ib_l]) : 0.0f;
-                na[v] = wa * gdiag[x][v];
-                nbm[v] = wb * gdiag[x][v];
+                na[v] = (ia_i < L && ia_l < ia_i) ? bc * fast_exp(gc - gq[v]) * gdiag[x][v] : 0.0f;
+                nbm[v] = (ib_i < L && ib_l < ib_i) ? bq[v] * fast_exp(gq[v] - gc) * gdiag[x][v] : 0.0f;
                 ia[v] = ia_i == ia_l ? 1.0f : 0.0f;
             }
             const f32x4_t p = unit_lower_inverse16(na, nbm, ia, c16, lq);
@@ -722,7 +740,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
-                const float bi = i < L ? sB[i] : 0.0f;
+                const float bi = sB[i];   // zero beyond the context
                 acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
                 acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
             }

@@ -152,7 +152,7 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
     constexpr int CH = 32;   // records per chunk
     __shared__ int sBlk[NW][MAX_BLOCKS];
 
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;   // (a scalar)
     const int lm = lane % 16, lq = lane / 16;
     const int lb = logical_block();
     const int b = lb / a.Hv;

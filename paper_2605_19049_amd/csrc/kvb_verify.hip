@@ -38,7 +38,7 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     __shared__ int sBlk[NW][MAX_BLOCKS];
     __shared__ float sGc[TAIL ? NW : 1][TMX];   // per-wave table for the keys beyond the register window
 
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;   // (a scalar)
     const int lb = logical_block();
     const int b = lb / a.Hv;
     const int h = lb % a.Hv;
