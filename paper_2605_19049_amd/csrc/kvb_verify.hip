@@ -19,8 +19,8 @@ namespace kvb_impl {
 // lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives C[4*(l/16)+v][l%16].
 // ---------------------------------------------------------------------------
 template <int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
-// (register budget of 4 waves per SIMD for the variants that stream the state through a half window)
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WREC <= 32 && HAS_STATE ? 4 : 1)))
+// (register budgets: 4 waves per SIMD with a record window of 16 or 32, 3 with the 64-record window)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(!HAS_STATE ? 1 : WREC <= 32 ? 4 : 3)))
 void kvb_verify_mfma_kernel(const StepArgs a)
 {
     constexpr int D = 128;
@@ -29,7 +29,7 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     constexpr int NTW = ((WREC + TMX + 15) / 16 + NW - 1) / NW;  // tiles per wave held in registers
     constexpr int WQ = WREC / 4;                              // record quads held in registers
     constexpr bool TAIL = WREC >= 64;
-    constexpr bool EARLY = HAS_STATE && WREC <= 32;   // state loads issued before the fill is known
+    constexpr bool EARLY = HAS_STATE;   // state loads issued before the fill is known
     static_assert(TMX == 8, "row m of W is draft m % 8");
 
     __shared__ __attribute__((aligned(16))) float sW[D][16];
@@ -150,8 +150,6 @@ void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int i = 0; i < TMX; ++i)
         v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + colf];
-    if constexpr (HAS_STATE && !EARLY)
-        issue_state();
     __builtin_amdgcn_sched_barrier(0);
 
     // Cumulative log decays and betas of the drafts as wave-uniform values read from the lanes
@@ -335,8 +333,6 @@ void kvb_verify_mfma_kernel(const StepArgs a)
         acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.x : 0.0f, acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.y : 0.0f, acc1, 0, 0, 0);
     }
-    if constexpr (HAS_STATE && !EARLY)
-        state_rows();
     // acc*[v] = row m = 4 lq + v, column col2 (+1)
 #pragma unroll
     for (int v = 0; v < 4; ++v)
