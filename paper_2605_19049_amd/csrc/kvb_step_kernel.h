@@ -564,23 +564,67 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const int32_t *slot_arg, i
                 }
                 l_done = LT * KP;
             }
-            for (int l0 = l_done; l0 < m; l0 += LT) {
-                __syncthreads();
-                // records before f come back from memory (written by earlier calls)
+            if constexpr (NG == LT) {
+              if (l_done < m) {   // uniform
+                // records before f come back from memory (written by earlier calls): thread (grp, sub)
+                // brings 8 elements of record l0 + grp, and the next tile is requested before this
+                // one is applied, so its round trip hides under the multiply-adds
+                const int lmax = f > 0 ? f - 1 : 0;   // requests are clamped; rows >= f are not used
+                int lr = min(l_done + grp, lmax);
+                size_t rowr = ru(lr);
+                Raw8<TIn> kq = load_raw8(kb + rk(lr) * D + 8 * sub);
+                float4 uq0 = up[rowr * LPR + 2 * sub];
+                float4 uq1 = up[rowr * LPR + 2 * sub + 1];
+                float Gq = Gbuf[rowr];
+                for (int l0 = l_done; l0 < m; l0 += LT) {
+                    __syncthreads();
+                    const int l = l0 + grp;
+                    if (l != f) {   // row f of the tile belongs to inject_new
+                        float kx[8];
+                        unpack8(kq, kx);
+                        const float w = l < f ? expf(Gc[0] - Gq) : 0.0f;
 #pragma unroll
-                for (int x = 0; x < EPT; ++x) {
-                    const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
-                    if (l < f) {
-                        kh[idx / D][e] = expf(Gc[0] - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
-                        uu[idx / D][e] = ub[ru(l) * D + e];
-                    } else if (l > f) {
-                        kh[idx / D][e] = 0.0f;
-                        uu[idx / D][e] = 0.0f;
+                        for (int e = 0; e < 8; ++e)
+                            kh[grp][8 * sub + e] = l < f ? w * kx[e] : 0.0f;
+                        // (component by component: a select between two float4 objects is compiled
+                        // as a select between their addresses, which puts them in scratch memory)
+                        const bool in = l < f;
+                        *reinterpret_cast<float4 *>(&uu[grp][8 * sub]) = make_float4(
+                            in ? uq0.x : 0.0f, in ? uq0.y : 0.0f, in ? uq0.z : 0.0f, in ? uq0.w : 0.0f);
+                        *reinterpret_cast<float4 *>(&uu[grp][8 * sub + 4]) = make_float4(
+                            in ? uq1.x : 0.0f, in ? uq1.y : 0.0f, in ? uq1.z : 0.0f, in ? uq1.w : 0.0f);
                     }
+                    inject_new(l0);
+                    // (the request past the last tile re-reads a valid record and is dropped)
+                    lr = min(l0 + LT + grp, lmax);
+                    rowr = ru(lr);
+                    kq = load_raw8(kb + rk(lr) * D + 8 * sub);
+                    uq0 = up[rowr * LPR + 2 * sub];
+                    uq1 = up[rowr * LPR + 2 * sub + 1];
+                    Gq = Gbuf[rowr];
+                    __syncthreads();
+                    apply_tile(l0);
                 }
-                inject_new(l0);
-                __syncthreads();
-                apply_tile(l0);
+              }
+            } else {
+                for (int l0 = l_done; l0 < m; l0 += LT) {
+                    __syncthreads();
+                    // records before f come back from memory (written by earlier calls)
+#pragma unroll
+                    for (int x = 0; x < EPT; ++x) {
+                        const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
+                        if (l < f) {
+                            kh[idx / D][e] = expf(Gc[0] - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
+                            uu[idx / D][e] = ub[ru(l) * D + e];
+                        } else if (l > f) {
+                            kh[idx / D][e] = 0.0f;
+                            uu[idx / D][e] = 0.0f;
+                        }
+                    }
+                    inject_new(l0);
+                    __syncthreads();
+                    apply_tile(l0);
+                }
             }
             float4 *sw = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
 #pragma unroll
