@@ -274,9 +274,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 #pragma unroll
     for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
         const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
-        kst[p] = u32x4_t{0u, 0u, 0u, 0u};
-        if (p < nb)   // uniform
-            kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
+        // (no branch around a load: at the join the compiler waits for every load in flight, which
+        // would make the passes take their round trips one after the other; blocks past the context
+        // re-read its last row from the cache)
+        kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
     }
     // Q is not staged: the waves read the rows of their q.k tiles straight from memory in the
     // operand layout of the matrix instruction (row 16 d + c16, k = 8 lq + 32 step); a block of
@@ -294,9 +295,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
         const uint32_t o = (uint32_t)min(16 * d + c16, L - 1) * qk_stride + 8 * lq;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            qop[n - 1][st] = u32x4_t{0u, 0u, 0u, 0u};
-            if (t >= 6 && d < nb)   // uniform
-                qop[n - 1][st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
+            qop[n - 1][st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
         }
     }
     const int col2 = 32 * wave + 2 * c16;
@@ -363,10 +362,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     for (int d = 0; d < NB; ++d)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            v_raw[d][v] = 0u;
-            if (d < nb)   // uniform
-                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
-                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+            v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
         }
 
     // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
