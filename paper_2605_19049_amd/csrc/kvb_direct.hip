@@ -566,9 +566,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
     for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
         const uint32_t o = (uint32_t)min(16 * p + srow, L - 1) * qk_stride + 8 * sc8;
-        kst[p] = u32x4_t{0u, 0u, 0u, 0u};
-        if (p < nb)   // uniform
-            kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);
+        kst[p] = *reinterpret_cast<const u32x4_t *>(kbase + o);   // (no branch around a load, as above)
     }
     // cumulative log decay and beta: wave 0 takes tokens 0..63, wave 1 tokens 64..127 (it adds
     // the sum of the first 64 decays, which it forms itself)
@@ -623,11 +621,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         pair_of(t, d, e, isq);
         const uint32_t o = (uint32_t)min(16 * d + c16, L - 1) * qk_stride + 8 * lq;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            qq[st] = u32x4_t{0u, 0u, 0u, 0u};
-            if (isq && d < nb)   // uniform
-                qq[st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
-        }
+        for (int st = 0; st < 4; ++st)   // (also for k.k tiles and empty blocks: no branch around a load)
+            qq[st] = *reinterpret_cast<const u32x4_t *>(qbase + o + 32 * st);
     };
     f32x4_t gsh[NTPW];
     u32x4_t qa[4], qb[4];
@@ -668,10 +663,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     for (int d = 0; d < NB; ++d)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            v_raw[d][v] = 0u;
-            if (d < nb)   // uniform
-                v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
-                    vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
+            v_raw[d][v] = *reinterpret_cast<const uint32_t *>(
+                vbase + (uint32_t)min(16 * d + 4 * lq + v, L - 1) * v_stride + col2);
         }
 
     // weights and masks.  A-form element of tile (d, e): row i = 16 d + c16, column l = 16 e + 4 lq + v.
