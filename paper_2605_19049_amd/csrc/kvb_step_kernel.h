@@ -38,7 +38,8 @@ __device__ __forceinline__ float group_sum(float x)
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
 template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
-__global__ __launch_bounds__(NT) void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg,
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(TM == 1 && WREC == 64 && HAS_STATE ? 3 : 1)))
+void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg,
                                                       const StepArgs a)
 {
     // The three leading arguments repeat a.slot, a.Hv and the grid size: as plain leading kernel
@@ -284,21 +285,41 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const int32_t *slot_arg, i
                 cQ[0][l] = w * dq;
             }
         }
-        for (int l = KP * NG + grp; TAIL && l < f; l += NG) {   // records beyond the register window
-            float kx[8];
-            load8(kb + rk(l) * D + 8 * sub, kx);
-            float dkk = 0.0f, dq = 0.0f;
+        if constexpr (TAIL) {
+            // records beyond the register window: all their passes are requested together (clamped,
+            // no branch around the loads), so a long buffer costs one more round trip, not one per pass
+            constexpr int KT = (KVB_MAX_CAP - KP * NG + NG - 1) / NG;
+            if (f > KP * NG) {   // uniform
+                Raw8<TIn> kt_raw[KT];
+                float Gt[KT];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                dkk = fmaf(kx[e], k8[e], dkk);
-                dq = fmaf(kx[e], q8[e], dq);
-            }
-            dkk = group_sum<GL>(dkk);
-            dq = group_sum<GL>(dq);
-            if (sub == 0) {
-                const float w = expf(Gc[0] - Gbuf[ru(l)]);
-                cK[0][l] = w * dkk;
-                cQ[0][l] = w * dq;
+                for (int x = 0; x < KT; ++x) {
+                    const int l = (KP + x) * NG + grp;
+                    const int lc = l < f ? l : 0;
+                    kt_raw[x] = load_raw8(kb + rk(lc) * D + 8 * sub);
+                    Gt[x] = Gbuf[ru(lc)];
+                }
+#pragma unroll
+                for (int x = 0; x < KT; ++x) {
+                    const int l = (KP + x) * NG + grp;
+                    if ((KP + x) * NG < f) {   // uniform
+                        float kx[8];
+                        unpack8(kt_raw[x], kx);
+                        float dkk = 0.0f, dq = 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            dkk = fmaf(kx[e], k8[e], dkk);
+                            dq = fmaf(kx[e], q8[e], dq);
+                        }
+                        dkk = group_sum<GL>(dkk);
+                        dq = group_sum<GL>(dq);
+                        if (sub == 0 && l < f) {
+                            const float w = expf(Gc[0] - Gt[x]);
+                            cK[0][l] = w * dkk;
+                            cQ[0][l] = w * dq;
+                        }
+                    }
+                }
             }
         }
     } else {
@@ -401,13 +422,31 @@ __global__ __launch_bounds__(NT) void kvb_step_kernel(const int32_t *slot_arg, i
             }
         }
     }
-    for (int l = UP * RPP + rg; TAIL && l < f; l += RPP) {
-        const float4 u = up[ru(l) * LPR + c4];
+    if constexpr (TAIL) {
+        // delta values beyond the register window, four passes to a round trip
+        constexpr int UT = (KVB_MAX_CAP - UP * RPP + RPP - 1) / RPP;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i < T) {
-                fma4(accU[i], -cK[i][l], u);
-                fma4(accO[i], cQ[i][l], u);
+        for (int x0 = 0; x0 < UT; x0 += 4) {
+            if ((UP + x0) * RPP < f) {   // uniform
+                float4 ut[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int l = (UP + x0 + j) * RPP + rg;
+                    ut[j] = up[ru(l < f ? l : 0) * LPR + c4];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int l = (UP + x0 + j) * RPP + rg;
+                    if (x0 + j < UT && l < f) {
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) {
+                            if (i < T) {
+                                fma4(accU[i], -cK[i][l], ut[j]);
+                                fma4(accO[i], cQ[i][l], ut[j]);
+                            }
+                        }
+                    }
+                }
             }
         }
     }

@@ -326,12 +326,23 @@ void kvb_verify_mfma_kernel(const StepArgs a)
             acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uq[sq].y : 0.0f, acc1, 0, 0, 0);
         }
     }
-    for (int sq = WQ; TAIL && sq < nquad; ++sq) {
-        const int l = 4 * sq + lq;
-        const float2 u = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
-        const float aw = cW[l][lm];
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.x : 0.0f, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u.y : 0.0f, acc1, 0, 0, 0);
+    // records beyond the register window: four quads to a round trip (requested together, clamped)
+    for (int s0 = WQ; TAIL && s0 < nquad; s0 += 4) {
+        float2 u4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int l = 4 * (s0 + j) + lq;
+            u4[j] = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int l = 4 * (s0 + j) + lq;   // < 4 * 35 + 4 = 144 rows of cW
+            if (s0 + j < nquad) {   // uniform
+                const float aw = cW[l][lm];
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u4[j].x : 0.0f, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, l < f ? u4[j].y : 0.0f, acc1, 0, 0, 0);
+            }
+        }
     }
     // acc*[v] = row m = 4 lq + v, column col2 (+1)
 #pragma unroll
