@@ -38,6 +38,7 @@ __device__ __forceinline__ float group_sum(float x)
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
 template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
+// (register budget: the 64-record decode variants sit at the edge of three workgroups per CU; hold them there)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(TM == 1 && WREC == 64 && HAS_STATE ? 3 : 1)))
 void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg,
                                                       const StepArgs a)
