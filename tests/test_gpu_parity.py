@@ -60,6 +60,8 @@ def test_tiny_fp32_decode_flush(C, fused):
     (32, "bf16", 3, 1, 3, 8, 20),
     (128, "bf16", 2, 1, 1, 64, 70),
     (128, "bf16", 2, 2, 4, 128, 130),
+    (64, "bf16", 2, 1, 2, 100, 110),     # records beyond the 64-record window at the smaller head sizes
+    (32, "f32", 2, 1, 1, 128, 130),
 ])
 @pytest.mark.parametrize("fused", [False, True])
 def test_decode_flush_shapes(d, in_dtype, B, Hk, Hv, C, steps, fused):
