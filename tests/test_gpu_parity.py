@@ -730,6 +730,13 @@ def test_largest_buffer_and_most_drafts():
     e = _verify_case(B=3, Hk=1, Hv=2, d=128, C=40, cap=48, T=8, in_dtype="f32", seed=98, fill_hi=39)
     say("cap=48 T=8 fp32 rel err out/u/state: %.2e %.2e %.2e" % e)
     assert max(e) < H.TOL["f32"]
+    # the vector-ALU verify path (head size 64) with more than 64 buffered records
+    e = _verify_case(B=3, Hk=1, Hv=2, d=64, C=96, cap=100, T=4, in_dtype="bf16", seed=100, fill_hi=95)   # fills 95, 88, 55
+    say("cap=100 T=4 d=64 rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["bf16"]
+    e = _verify_case(B=2, Hk=1, Hv=1, d=128, C=100, cap=104, T=4, in_dtype="f32", seed=108, fill_hi=99)    # fills 99, 61
+    say("cap=104 T=4 d=128 fp32 rel err out/u/state: %.2e %.2e %.2e" % e)
+    assert max(e) < H.TOL["f32"]
 
 
 def test_kv_only_verify_and_stream_hint_do_not_change_results():
