@@ -2,10 +2,12 @@
  * kvb -- KVBuffer-style Gated DeltaNet decoding for AMD MI355X (gfx950).
  *
  * C ABI of the library.  Every pointer marked "device" is device memory owned
- * by the caller; the compute calls never allocate, free or synchronise, keep no
- * global state, and enqueue all work on the caller's HIP stream (`stream` is a
- * hipStream_t passed as void*; NULL = the default stream).  The two structs are
- * host memory and are read only during the call.
+ * by the caller; the compute calls never allocate, free or synchronise, and
+ * enqueue all work on the caller's HIP stream (`stream` is a hipStream_t passed
+ * as void*; NULL = the default stream).  The two structs are host memory and are
+ * read only during the call.  The only state the library keeps is two
+ * thread-local words on the host: the timer armed for the calling thread's next
+ * launch (kvb_timer_arm) and the HIP error code behind the last KVB_EHIP.
  *
  * Notation (paper Sec. 2.1, Sec. 3, App. A.1).  For one request and one v-head:
  *   S0    the committed state, dk x dv, fp32                (the "state slot", Sec. 2.2)
@@ -34,7 +36,7 @@
 extern "C" {
 #endif
 
-#define KVB_VERSION 110 /* 110: kvb_store carries the block-table fields; kvb_verify_tree, kvb_compact */
+#define KVB_VERSION 120 /* 120: fp16 inputs, 16-bit delta-value records and outputs (kvb_shape.rec_dtype) */
 
 /* return codes */
 #define KVB_OK            0
@@ -42,9 +44,14 @@ extern "C" {
 #define KVB_EUNSUPPORTED (-2) /* head size or dtype combination that is not compiled    */
 #define KVB_EHIP         (-3) /* the HIP runtime refused the launch                     */
 
-/* element types of q, k, v and of the buffered keys */
+/* element types: of q, k, v and the buffered keys (in_dtype), of the buffered delta values
+ * (rec_dtype) and of the outputs (out_dtype).  The paper's implementation keeps a fp32 state
+ * and fp16 vectors and records (Sec. 4.1; caption of the GDN memory-profile table, App. A.2):
+ * that is in = rec = out = KVB_F16.  A 16-bit rec_dtype or out_dtype must equal in_dtype;
+ * KVB_F32 is always allowed for both.  The state is fp32 throughout. */
 #define KVB_F32  0
 #define KVB_BF16 1
+#define KVB_F16  2
 
 #define KVB_MAX_CAP        128 /* largest `cap` (the paper buffers at most d records, Sec. 3.4) */
 #define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
@@ -71,8 +78,12 @@ typedef struct kvb_shape {
     int32_t dk;        /* key/query head size;   compiled: dk == dv in {32, 64, 128}       */
     int32_t dv;        /* value head size                                                  */
     int32_t cap;       /* records one request's buffer can hold, 1..KVB_MAX_CAP            */
-    int32_t in_dtype;  /* KVB_F32 or KVB_BF16: type of q, k, v and of buf_k                */
-    int32_t out_dtype; /* KVB_F32 only                                                     */
+    int32_t in_dtype;  /* KVB_F32, KVB_BF16 or KVB_F16: type of q, k, v and of buf_k       */
+    int32_t out_dtype; /* type of `out`: KVB_F32, or in_dtype if that is a 16-bit type     */
+    int32_t rec_dtype; /* type of buf_u: KVB_F32, or in_dtype if that is a 16-bit type.    */
+                       /* A 16-bit record holds the delta value rounded to nearest even;   */
+                       /* every later use (the token's own output included) reads that     */
+                       /* rounded value, so a record is all that later calls depend on.    */
     float   scale;     /* multiplies every output (1.0 = the paper's formulas)             */
 } kvb_shape;
 
@@ -80,7 +91,7 @@ typedef struct kvb_store {
     float   *state;   /* device [n_slots, Hv, dk, dv] fp32, dv contiguous.  May be NULL for
                          kvb_decode / kvb_verify: KV-only mode, S0 taken as zero (Sec. 3.4). */
     void    *buf_k;   /* device [n_slots, Hk, cap, dk] in_dtype                             */
-    float   *buf_u;   /* device [n_slots, Hv, cap, dv] fp32                                 */
+    void    *buf_u;   /* device [n_slots, Hv, cap, dv] rec_dtype                            */
     float   *buf_G;   /* device [n_slots, Hv, cap]     fp32                                 */
     int32_t *fill;    /* device [n_slots]; 0..cap between calls.  While a call that changes
                          fill runs, bits 16.. of the word count the workgroups that have
@@ -119,7 +130,7 @@ typedef struct kvb_store {
  * output and record f = (k, u, G_f), then fill = f + 1.  Never writes `state`.
  *   q, k  device [B, Hk, dk] in_dtype      v    device [B, Hv, dv] in_dtype
  *   g     device [B, Hv] fp32 log decay    beta device [B, Hv] fp32
- *   out   device [B, Hv, dv] fp32
+ *   out   device [B, Hv, dv] out_dtype
  * A request with f == cap is skipped: its out row and buffer are left as they
  * are and status[slot] gets KVB_STATUS_OVERFLOW.
  */
@@ -165,7 +176,7 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
  * `state`) untouched: committing is kvb_flush(accepted, ...).
  *   T     1..KVB_MAX_DRAFTS
  *   q, k  device [B, T, Hk, dk]   v device [B, T, Hv, dv]   g, beta device [B, T, Hv]
- *   out   device [B, T, Hv, dv] fp32
+ *   out   device [B, T, Hv, dv] out_dtype
  * A request with f + T > cap is skipped with KVB_STATUS_OVERFLOW.
  */
 int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
@@ -216,7 +227,7 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
  *   len   device int32 [B], 0..Lmax        Lmax 1..min(cap, KVB_MAX_DIRECT_LEN); above 64 only for
  *         bf16 inputs with d = 128 (KVB_EUNSUPPORTED otherwise)
  *   q, k  device [B, Lmax, Hk, dk]  v device [B, Lmax, Hv, dv]  g, beta device [B, Lmax, Hv]
- *   out   device [B, Lmax, Hv, dv] fp32; rows >= len[b] are not written
+ *   out   device [B, Lmax, Hv, dv] out_dtype; rows >= len[b] are not written
  * len[b] outside 0..Lmax is clamped to Lmax with KVB_STATUS_OVERFLOW.
  */
 int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,

@@ -12,7 +12,8 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["kvb_api.hip", "kvb_step_bf16.hip", "kvb_step_f32.hip", "kvb_verify.hip", "kvb_flush.hip", "kvb_direct.hip"]
+SOURCES = ["kvb_api.hip", "kvb_step_bf16.hip", "kvb_step_bf16_r16.hip", "kvb_step_f16.hip", "kvb_step_f16_r16.hip",
+           "kvb_step_f32.hip", "kvb_verify_bf16.hip", "kvb_verify_f16.hip", "kvb_flush.hip", "kvb_direct.hip"]
 LIB = os.path.join(HERE, "libkvb.so")
 
 HIPCC_FLAGS = [

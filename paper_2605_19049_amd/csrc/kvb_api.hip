@@ -5,6 +5,7 @@
 namespace kvb_impl {
 
 thread_local kvb_timer *g_armed = nullptr;
+thread_local hipError_t g_launch_status = hipSuccess;
 
 }  // namespace kvb_impl
 
@@ -42,9 +43,12 @@ int check_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot)
         return KVB_EINVAL;
     if ((long long)sh->B * sh->Hv > 0x7FFFFFFFLL)
         return KVB_EINVAL;
-    if (sh->in_dtype != KVB_F32 && sh->in_dtype != KVB_BF16)
+    if (sh->in_dtype != KVB_F32 && sh->in_dtype != KVB_BF16 && sh->in_dtype != KVB_F16)
         return KVB_EUNSUPPORTED;
-    if (sh->out_dtype != KVB_F32)
+    // records and outputs: fp32, or the 16-bit type of the inputs
+    if (sh->out_dtype != KVB_F32 && (sh->in_dtype == KVB_F32 || sh->out_dtype != sh->in_dtype))
+        return KVB_EUNSUPPORTED;
+    if (sh->rec_dtype != KVB_F32 && (sh->in_dtype == KVB_F32 || sh->rec_dtype != sh->in_dtype))
         return KVB_EUNSUPPORTED;
     if (sh->dk != sh->dv || (sh->dk != 32 && sh->dk != 64 && sh->dk != 128))
         return KVB_EUNSUPPORTED;
@@ -62,7 +66,9 @@ int check_tokens(const void *q, const void *k, const void *v, const float *g, co
 }
 
 // Whether the state should be streamed past the caches: the caller's hint, else by this
-// call's own state footprint against the 256 MB last-level cache.
+// call's own state footprint against the 256 MB last-level cache.  The switch sits at 1.5 times
+// the cache: a state of 256 MiB re-read every step still finds most of itself there and runs
+// faster with plain loads, one of 512 MiB does not.
 bool stream_state(const kvb_shape *sh, const kvb_store *st)
 {
     if (st->flags & KVB_STORE_STREAM)
@@ -80,15 +86,23 @@ Store dev_store(const kvb_store *st)
                  st->block_table ? st->n_blocks : 0};
 }
 
+// The status of the launch this thread has just made (what the launch call itself returned:
+// an error some other library left behind in the runtime is neither reported nor cleared).
 int finish_launch()
 {
-    const hipError_t e = hipGetLastError();
+    const hipError_t e = g_launch_status;
     if (e != hipSuccess) {
         g_last_hip_error = e;
         return KVB_EHIP;
     }
     return KVB_OK;
 }
+
+// Every compute entry point ends with no timer armed: a call that returns before it launches
+// (bad arguments, B = 0) must not leave its timer to some later, unrelated launch.
+struct DisarmOnExit {
+    ~DisarmOnExit() { g_armed = nullptr; }
+};
 
 int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, int T, const void *q,
                 const void *k, const void *v, const float *g, const float *beta, void *out, void *stream,
@@ -104,16 +118,20 @@ int step_common(const kvb_shape *sh, const kvb_store *st, const int32_t *slot, i
         return KVB_EINVAL;
     if (sh->B == 0)
         return KVB_OK;
-    StepArgs a{dev_store(st), slot, q, k, v, g, beta, static_cast<float *>(out), sh->Hk, sh->Hv, sh->cap, T,
+    StepArgs a{dev_store(st), slot, q, k, v, g, beta, out, sh->out_dtype == KVB_F32, sh->Hk, sh->Hv, sh->cap, T,
                sh->scale, advance, threshold, stream_state(sh, st) ? 1 : 0,
                // chain: g stands in as a readable array of at least B*T words whose values are ignored
                parent ? parent : reinterpret_cast<const int32_t *>(g), parent ? 1 : 0};
     const int blocks = sh->B * sh->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (sh->dk == 128 && sh->in_dtype == KVB_BF16 && T > 1)   // several drafts: the matrix-core kernel
-        launch_verify_mfma(a, blocks, hs);
+    g_launch_status = hipSuccess;
+    if (sh->dk == 128 && sh->in_dtype != KVB_F32 && T > 1)   // several drafts: the matrix-core kernel
+        rc = dispatch_types16(sh->in_dtype, sh->rec_dtype,
+                              [&]<typename TIn, typename TRec>() { launch_verify_typed<TIn, TRec>(a, blocks, hs); });
     else
-        rc = sh->in_dtype == KVB_BF16 ? launch_step_bf16(sh->dk, a, blocks, hs) : launch_step_f32(sh->dk, a, blocks, hs);
+        rc = dispatch_types(sh->in_dtype, sh->rec_dtype, [&]<typename TIn, typename TRec>() {
+            launch_step_typed<TIn, TRec>(sh->dk, a, blocks, hs);   // (the head size was checked above)
+        });
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
@@ -126,6 +144,7 @@ extern "C" {
 int kvb_decode(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, const void *q, const void *k,
                const void *v, const float *g, const float *beta, void *out, void *stream)
 {
+    DisarmOnExit disarm;
     return step_common(shape, store, slot, 1, q, k, v, g, beta, out, stream, 1);
 }
 
@@ -133,6 +152,7 @@ int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32
                      const void *k, const void *v, const float *g, const float *beta, void *out,
                      int32_t threshold, void *stream)
 {
+    DisarmOnExit disarm;
     if (!shape || !store)
         return KVB_EINVAL;
     if (!store->state || threshold < 1 || threshold > shape->cap)
@@ -143,6 +163,7 @@ int kvb_decode_flush(const kvb_shape *shape, const kvb_store *store, const int32
 int kvb_verify(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T, const void *q,
                const void *k, const void *v, const float *g, const float *beta, void *out, void *stream)
 {
+    DisarmOnExit disarm;
     return step_common(shape, store, slot, T, q, k, v, g, beta, out, stream, 0);
 }
 
@@ -150,6 +171,7 @@ int kvb_verify_tree(const kvb_shape *shape, const kvb_store *store, const int32_
                     const int32_t *parent, const void *q, const void *k, const void *v, const float *g,
                     const float *beta, void *out, void *stream)
 {
+    DisarmOnExit disarm;
     if (!parent || !aligned(parent, 4))
         return KVB_EINVAL;
     return step_common(shape, store, slot, T, q, k, v, g, beta, out, stream, 0, 0, parent);
@@ -158,6 +180,7 @@ int kvb_verify_tree(const kvb_shape *shape, const kvb_store *store, const int32_
 int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, int32_t T,
                 const int32_t *path, const int32_t *path_len, void *stream)
 {
+    DisarmOnExit disarm;
     int rc = check_common(shape, store, slot);
     if (rc != KVB_OK)
         return rc;
@@ -170,7 +193,8 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
     CompactArgs a{dev_store(store), slot, path, path_len, shape->Hk, shape->Hv, shape->cap, T};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    rc = launch_compact(shape->dk, shape->in_dtype, a, blocks, hs);
+    g_launch_status = hipSuccess;
+    rc = launch_compact(shape->dk, shape->in_dtype, shape->rec_dtype, a, blocks, hs);
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
@@ -179,6 +203,7 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
 int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slot, const int32_t *accepted,
               int32_t threshold, void *stream)
 {
+    DisarmOnExit disarm;
     int rc = check_common(shape, store, slot);
     if (rc != KVB_OK)
         return rc;
@@ -193,7 +218,8 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
     FlushArgs a{dev_store(store), slot, accepted, shape->Hk, shape->Hv, shape->cap, threshold};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    rc = launch_flush(shape->dk, shape->in_dtype, a, blocks, hs);
+    g_launch_status = hipSuccess;
+    rc = launch_flush(shape->dk, shape->in_dtype, shape->rec_dtype, a, blocks, hs);
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
@@ -203,6 +229,7 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
                int32_t Lmax, const void *q, const void *k, const void *v, const float *g, const float *beta,
                void *out, void *stream)
 {
+    DisarmOnExit disarm;
     int rc = check_common(shape, store, slot);
     if (rc != KVB_OK)
         return rc;
@@ -215,11 +242,12 @@ int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *sl
         return KVB_EINVAL;
     if (shape->B == 0)
         return KVB_OK;
-    DirectArgs a{dev_store(store), slot, len, q, k, v, g, beta, static_cast<float *>(out), shape->Hk, shape->Hv,
-                 shape->cap, Lmax, shape->scale};
+    DirectArgs a{dev_store(store), slot, len, q, k, v, g, beta, out, shape->out_dtype == KVB_F32, shape->Hk,
+                 shape->Hv, shape->cap, Lmax, shape->scale};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    rc = launch_direct(shape->dk, shape->in_dtype, a, blocks, hs);
+    g_launch_status = hipSuccess;
+    rc = launch_direct(shape->dk, shape->in_dtype, shape->rec_dtype, a, blocks, hs);
     if (rc != KVB_OK)
         return rc;
     return finish_launch();
@@ -235,6 +263,7 @@ int kvb_timer_create(kvb_timer **timer)
         e = hipEventCreate(&t->stop);
     if (e != hipSuccess) {
         g_last_hip_error = e;
+        (void)hipGetLastError();   // (as in kvb_timer_read)
         if (t->start)
             (void)hipEventDestroy(t->start);
         delete t;
@@ -260,6 +289,7 @@ int kvb_timer_read(kvb_timer *timer, float *microseconds)
         e = hipEventElapsedTime(&ms, timer->start, timer->stop);
     if (e != hipSuccess) {
         g_last_hip_error = e;
+        (void)hipGetLastError();   // this call's own error: not left behind for the caller's next HIP call
         return KVB_EHIP;
     }
     *microseconds = ms * 1000.0f;

@@ -29,6 +29,9 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+
 #include "kvb.h"
 
 struct kvb_timer {
@@ -45,11 +48,51 @@ constexpr int TICKET_ONE = 1 << 16;
 struct bf16_t {
     uint16_t bits;
 };
+struct f16_t {
+    uint16_t bits;
+};
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float((uint32_t)x.bits << 16); }
+__device__ __forceinline__ float to_f32(f16_t x) { return (float)__builtin_bit_cast(_Float16, x.bits); }
 
-// 8 consecutive elements starting at p (p is 16-byte aligned for bf16, 32 for fp32).
+// Rounding to a storage type, to nearest even (the hardware conversions of gfx950).
+template <typename T>
+__device__ __forceinline__ T from_f32(float x);
+template <>
+__device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return bf16_t{__builtin_bit_cast(uint16_t, (__bf16)x)}; }
+template <>
+__device__ __forceinline__ f16_t from_f32<f16_t>(float x) { return f16_t{__builtin_bit_cast(uint16_t, (_Float16)x)}; }
+// x as the storage type T will hold it
+template <typename T>
+__device__ __forceinline__ float rounded_to(float x) { return to_f32(from_f32<T>(x)); }
+
+// The two 16-bit elements packed in one word, and two floats packed into one.
+template <typename T>
+__device__ __forceinline__ float2 unpack_pair(uint32_t w)
+{
+    if constexpr (__is_same(T, bf16_t)) {
+        return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xFFFF0000u));
+    } else {
+        const f16x2_t h = __builtin_bit_cast(f16x2_t, w);
+        return make_float2((float)h[0], (float)h[1]);
+    }
+}
+template <typename T>
+__device__ __forceinline__ uint32_t pack_pair(float lo, float hi)
+{
+    return (uint32_t)from_f32<T>(lo).bits | ((uint32_t)from_f32<T>(hi).bits << 16);
+}
+
+// 8 consecutive elements starting at p (p is 16-byte aligned for the 16-bit types, 32 for fp32).
 __device__ __forceinline__ void load8(const float *p, float (&o)[8])
 {
     const float4 a = *reinterpret_cast<const float4 *>(p);
@@ -57,46 +100,143 @@ __device__ __forceinline__ void load8(const float *p, float (&o)[8])
     o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
     o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
 }
-__device__ __forceinline__ void load8(const bf16_t *p, float (&o)[8])
-{
-    const uint4 w = *reinterpret_cast<const uint4 *>(p);
-    o[0] = __uint_as_float(w.x << 16); o[1] = __uint_as_float(w.x & 0xFFFF0000u);
-    o[2] = __uint_as_float(w.y << 16); o[3] = __uint_as_float(w.y & 0xFFFF0000u);
-    o[4] = __uint_as_float(w.z << 16); o[5] = __uint_as_float(w.z & 0xFFFF0000u);
-    o[6] = __uint_as_float(w.w << 16); o[7] = __uint_as_float(w.w & 0xFFFF0000u);
-}
 
 // The same 8 elements as untouched bits: issuing a load and converting its result are
 // kept apart so that no wait lands between two loads.
 template <typename T>
-struct Raw8;
+struct Raw8 {
+    uint4 w;
+};
 template <>
 struct Raw8<float> {
     float4 a, b;
-};
-template <>
-struct Raw8<bf16_t> {
-    uint4 w;
 };
 __device__ __forceinline__ Raw8<float> load_raw8(const float *p)
 {
     return Raw8<float>{*reinterpret_cast<const float4 *>(p), *reinterpret_cast<const float4 *>(p + 4)};
 }
-__device__ __forceinline__ Raw8<bf16_t> load_raw8(const bf16_t *p)
+template <typename T>
+__device__ __forceinline__ Raw8<T> load_raw8(const T *p)
 {
-    return Raw8<bf16_t>{*reinterpret_cast<const uint4 *>(p)};
+    return Raw8<T>{*reinterpret_cast<const uint4 *>(p)};
 }
 __device__ __forceinline__ void unpack8(const Raw8<float> &r, float (&o)[8])
 {
     o[0] = r.a.x; o[1] = r.a.y; o[2] = r.a.z; o[3] = r.a.w;
     o[4] = r.b.x; o[5] = r.b.y; o[6] = r.b.z; o[7] = r.b.w;
 }
-__device__ __forceinline__ void unpack8(const Raw8<bf16_t> &r, float (&o)[8])
+template <typename T>
+__device__ __forceinline__ void unpack8(const Raw8<T> &r, float (&o)[8])
 {
-    o[0] = __uint_as_float(r.w.x << 16); o[1] = __uint_as_float(r.w.x & 0xFFFF0000u);
-    o[2] = __uint_as_float(r.w.y << 16); o[3] = __uint_as_float(r.w.y & 0xFFFF0000u);
-    o[4] = __uint_as_float(r.w.z << 16); o[5] = __uint_as_float(r.w.z & 0xFFFF0000u);
-    o[6] = __uint_as_float(r.w.w << 16); o[7] = __uint_as_float(r.w.w & 0xFFFF0000u);
+    const float2 a = unpack_pair<T>(r.w.x), b = unpack_pair<T>(r.w.y), c = unpack_pair<T>(r.w.z), d = unpack_pair<T>(r.w.w);
+    o[0] = a.x; o[1] = a.y; o[2] = b.x; o[3] = b.y;
+    o[4] = c.x; o[5] = c.y; o[6] = d.x; o[7] = d.y;
+}
+template <typename T>
+__device__ __forceinline__ void load8(const T *p, float (&o)[8])
+{
+    unpack8(load_raw8(p), o);
+}
+
+// 4 and 2 consecutive elements of a record array (delta values), raw and converted.
+template <typename T>
+struct Raw4 {
+    uint2 w;
+};
+template <>
+struct Raw4<float> {
+    float4 a;
+};
+__device__ __forceinline__ Raw4<float> load_raw4(const float *p) { return Raw4<float>{*reinterpret_cast<const float4 *>(p)}; }
+template <typename T>
+__device__ __forceinline__ Raw4<T> load_raw4(const T *p) { return Raw4<T>{*reinterpret_cast<const uint2 *>(p)}; }
+__device__ __forceinline__ float4 unpack4(const Raw4<float> &r) { return r.a; }
+template <typename T>
+__device__ __forceinline__ float4 unpack4(const Raw4<T> &r)
+{
+    const float2 a = unpack_pair<T>(r.w.x), b = unpack_pair<T>(r.w.y);
+    return make_float4(a.x, a.y, b.x, b.y);
+}
+template <typename T>
+struct Raw2 {
+    uint32_t w;
+};
+template <>
+struct Raw2<float> {
+    float2 a;
+};
+__device__ __forceinline__ Raw2<float> load_raw2(const float *p) { return Raw2<float>{*reinterpret_cast<const float2 *>(p)}; }
+template <typename T>
+__device__ __forceinline__ Raw2<T> load_raw2(const T *p) { return Raw2<T>{*reinterpret_cast<const uint32_t *>(p)}; }
+__device__ __forceinline__ float2 unpack2r(const Raw2<float> &r) { return r.a; }
+template <typename T>
+__device__ __forceinline__ float2 unpack2r(const Raw2<T> &r) { return unpack_pair<T>(r.w); }
+
+// Stores of already-rounded or to-be-rounded values into an array of type T.
+__device__ __forceinline__ void store2(float *p, float x, float y) { *reinterpret_cast<float2 *>(p) = make_float2(x, y); }
+template <typename T>
+__device__ __forceinline__ void store2(T *p, float x, float y) { *reinterpret_cast<uint32_t *>(p) = pack_pair<T>(x, y); }
+__device__ __forceinline__ void store4(float *p, const float4 &v) { *reinterpret_cast<float4 *>(p) = v; }
+template <typename T>
+__device__ __forceinline__ void store4(T *p, const float4 &v)
+{
+    *reinterpret_cast<uint2 *>(p) = make_uint2(pack_pair<T>(v.x, v.y), pack_pair<T>(v.z, v.w));
+}
+__device__ __forceinline__ void store1(float *p, float x) { *p = x; }
+template <typename T>
+__device__ __forceinline__ void store1(T *p, float x) { *p = from_f32<T>(x); }
+
+// The output array has a run-time element type (KVB_F32 or the 16-bit input type TIn): the
+// stores sit at the end of every kernel, where a uniform branch costs nothing.
+template <typename TIn>
+struct Out {
+    void *p;
+    bool wide;   // fp32 elements
+    __device__ __forceinline__ void put1(size_t i, float x) const
+    {
+        if constexpr (sizeof(TIn) == 4) {
+            static_cast<float *>(p)[i] = x;
+        } else {
+            if (wide)
+                static_cast<float *>(p)[i] = x;
+            else
+                store1(static_cast<TIn *>(p) + i, x);
+        }
+    }
+    __device__ __forceinline__ void put2(size_t i, float x, float y) const
+    {
+        if constexpr (sizeof(TIn) == 4) {
+            store2(static_cast<float *>(p) + i, x, y);
+        } else {
+            if (wide)
+                store2(static_cast<float *>(p) + i, x, y);
+            else
+                store2(static_cast<TIn *>(p) + i, x, y);
+        }
+    }
+    __device__ __forceinline__ void put4(size_t i, const float4 &v) const
+    {
+        if constexpr (sizeof(TIn) == 4) {
+            store4(static_cast<float *>(p) + i, v);
+        } else {
+            if (wide)
+                store4(static_cast<float *>(p) + i, v);
+            else
+                store4(static_cast<TIn *>(p) + i, v);
+        }
+    }
+};
+
+// v_mfma_f32_16x16x32 on 16-bit operands of type T given as raw bits (8 elements per lane).
+template <typename T>
+__device__ __forceinline__ f32x4_t mfma16x32(const uint4 &a, const uint4 &b, const f32x4_t &c)
+{
+    if constexpr (__is_same(T, bf16_t))
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                       c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
+                                                      c, 0, 0, 0);
 }
 
 // One 16-byte piece of the state tile.  STREAM: non-temporal load, for a state that will
@@ -156,7 +296,8 @@ __device__ __forceinline__ void store_raw8(float *p, const Raw8<float> &r)
     *reinterpret_cast<float4 *>(p) = r.a;
     *reinterpret_cast<float4 *>(p + 4) = r.b;
 }
-__device__ __forceinline__ void store_raw8(bf16_t *p, const Raw8<bf16_t> &r)
+template <typename T>
+__device__ __forceinline__ void store_raw8(T *p, const Raw8<T> &r)
 {
     *reinterpret_cast<uint4 *>(p) = r.w;
 }
@@ -174,8 +315,8 @@ __device__ __forceinline__ int logical_block() { return logical_block(gridDim.x)
 
 struct Store {
     float *state;
-    void *buf_k;
-    float *buf_u;
+    void *buf_k;   // input type
+    void *buf_u;   // record type
     float *buf_G;
     int32_t *fill;
     int32_t *status;
@@ -235,6 +376,7 @@ __device__ __forceinline__ Pages<PAGED> make_pages(const Store &st, int s, int c
     if constexpr (PAGED) {
         if (lane < MAX_BLOCKS)
             tab[lane] = min(max(id, 0), st.n_blocks - 1);
+        __builtin_amdgcn_wave_barrier();   // the lookups below stay behind this store (same wave, so no more is needed)
         pg.bs = st.block_size;
         pg.lg = 31 - __builtin_clz(st.block_size);
     } else {
@@ -249,7 +391,8 @@ struct StepArgs {
     const int32_t *slot;
     const void *q, *k, *v;
     const float *g, *beta;
-    float *out;
+    void *out;
+    int32_t out_wide;   // fp32 outputs (otherwise the 16-bit input type)
     int32_t Hk, Hv, cap, T;
     float scale;
     int32_t advance;    // 1: decode (fill += T after the step); 0: verify (fill untouched)
@@ -275,7 +418,8 @@ struct DirectArgs {
     const int32_t *len;
     const void *q, *k, *v;
     const float *g, *beta;
-    float *out;
+    void *out;
+    int32_t out_wide;   // fp32 outputs (otherwise the 16-bit input type)
     int32_t Hk, Hv, cap, Lmax;
     float scale;
 };
@@ -288,26 +432,32 @@ struct CompactArgs {
     int32_t Hk, Hv, cap, T;
 };
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-
 // ---------------------------------------------------------------------------
 // launch plumbing (host)
 // ---------------------------------------------------------------------------
-// The timer that the calling thread armed for its next launch (kvb_api.hip).
+// The timer that the calling thread armed for its next launch, and what its last launch
+// returned (kvb_api.hip).
 extern thread_local kvb_timer *g_armed;
+extern thread_local hipError_t g_launch_status;
 
 // One kernel launch.  If this thread armed a timer, the launch carries its two events so
-// that they hold the kernel's own begin / end timestamps.
+// that they hold the kernel's own begin / end timestamps.  The runtime's return code is kept
+// in g_launch_status (the runtime's "last error" is left alone: it may hold some other
+// library's error, which is neither ours to report nor ours to clear).
 template <typename... Params, typename... Args>
 void launch(void (*kernel)(Params...), int blocks, hipStream_t stream, const Args &...a)
 {
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<std::remove_cv_t<Params>...> params{a...};
+    void *argv[sizeof...(Params)];
+    std::apply([&](auto &...p) { int i = 0; ((argv[i++] = &p), ...); }, params);
     kvb_timer *t = g_armed;
     g_armed = nullptr;
     if (t)
-        hipExtLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, t->start, t->stop, 0, a...);
+        g_launch_status = hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(NT), argv, 0,
+                                             stream, t->start, t->stop, 0);
     else
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(NT), 0, stream, a...);
+        g_launch_status = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(NT), argv, 0, stream);
 }
 
 // Picks the paged or the contiguous instance of a kernel template whose last parameter is PAGED;
@@ -320,33 +470,69 @@ void launch(void (*kernel)(Params...), int blocks, hipStream_t stream, const Arg
             launch(__VA_ARGS__, false>, blocks, stream, a);           \
     } while (0)
 
-// Calls f.template operator()<D, TIn>() for the compiled (head size, dtype) pairs.
+// The compiled (input type, record type) pairs: fp32 records with any input type, 16-bit records
+// of the input's own 16-bit type.  Calls f.template operator()<TIn, TRec>().
 template <typename F>
-int dispatch(int dk, int in_dtype, F &&f)
+int dispatch_types(int in_dtype, int rec_dtype, F &&f)
 {
-    const bool bf = in_dtype == KVB_BF16;
-    switch (dk) {
-    case 32:
-        bf ? f.template operator()<32, bf16_t>() : f.template operator()<32, float>();
-        return KVB_OK;
-    case 64:
-        bf ? f.template operator()<64, bf16_t>() : f.template operator()<64, float>();
-        return KVB_OK;
-    case 128:
-        bf ? f.template operator()<128, bf16_t>() : f.template operator()<128, float>();
-        return KVB_OK;
-    }
-    return KVB_EUNSUPPORTED;
+    const bool wide = rec_dtype == KVB_F32;
+    if (in_dtype == KVB_F32 && wide)
+        f.template operator()<float, float>();
+    else if (in_dtype == KVB_BF16 && wide)
+        f.template operator()<bf16_t, float>();
+    else if (in_dtype == KVB_BF16 && rec_dtype == KVB_BF16)
+        f.template operator()<bf16_t, bf16_t>();
+    else if (in_dtype == KVB_F16 && wide)
+        f.template operator()<f16_t, float>();
+    else if (in_dtype == KVB_F16 && rec_dtype == KVB_F16)
+        f.template operator()<f16_t, f16_t>();
+    else
+        return KVB_EUNSUPPORTED;
+    return KVB_OK;
+}
+// The same for the 16-bit input types alone (the matrix-core kernels).
+template <typename F>
+int dispatch_types16(int in_dtype, int rec_dtype, F &&f)
+{
+    const bool wide = rec_dtype == KVB_F32;
+    if (in_dtype == KVB_BF16 && wide)
+        f.template operator()<bf16_t, float>();
+    else if (in_dtype == KVB_BF16 && rec_dtype == KVB_BF16)
+        f.template operator()<bf16_t, bf16_t>();
+    else if (in_dtype == KVB_F16 && wide)
+        f.template operator()<f16_t, float>();
+    else if (in_dtype == KVB_F16 && rec_dtype == KVB_F16)
+        f.template operator()<f16_t, f16_t>();
+    else
+        return KVB_EUNSUPPORTED;
+    return KVB_OK;
 }
 
-// One launcher per translation unit.  Those that take (dk, in_dtype) return KVB_EUNSUPPORTED
-// for a pair that is not compiled; none of them checks the launch (the caller does).
-int launch_step_bf16(int dk, const StepArgs &a, int blocks, hipStream_t stream);                // kvb_step_bf16.hip
-int launch_step_f32(int dk, const StepArgs &a, int blocks, hipStream_t stream);                 // kvb_step_f32.hip
-void launch_verify_mfma(const StepArgs &a, int blocks, hipStream_t stream);                    // kvb_verify.hip (bf16, d = 128)
-int launch_flush(int dk, int in_dtype, const FlushArgs &a, int blocks, hipStream_t stream);    // kvb_flush.hip
-int launch_compact(int dk, int in_dtype, const CompactArgs &a, int blocks, hipStream_t stream);
-int launch_direct(int dk, int in_dtype, const DirectArgs &a, int blocks, hipStream_t stream);  // kvb_direct.hip
+// Calls f.template operator()<D, TIn, TRec>() for the compiled head sizes and type pairs.
+template <typename F>
+int dispatch(int dk, int in_dtype, int rec_dtype, F &&f)
+{
+    if (dk != 32 && dk != 64 && dk != 128)
+        return KVB_EUNSUPPORTED;
+    return dispatch_types(in_dtype, rec_dtype, [&]<typename TIn, typename TRec>() {
+        if (dk == 32)
+            f.template operator()<32, TIn, TRec>();
+        else if (dk == 64)
+            f.template operator()<64, TIn, TRec>();
+        else
+            f.template operator()<128, TIn, TRec>();
+    });
+}
+
+// One launcher per translation unit.  They return KVB_EUNSUPPORTED for a head size or type pair
+// that is not compiled; none of them checks the launch (the caller does).
+template <typename TIn, typename TRec>
+int launch_step_typed(int dk, const StepArgs &a, int blocks, hipStream_t stream);   // kvb_step_*.hip, one unit per pair
+template <typename TIn, typename TRec>
+void launch_verify_typed(const StepArgs &a, int blocks, hipStream_t stream);        // kvb_verify_*.hip (16-bit inputs, d = 128)
+int launch_flush(int dk, int in_dtype, int rec_dtype, const FlushArgs &a, int blocks, hipStream_t stream);    // kvb_flush.hip
+int launch_compact(int dk, int in_dtype, int rec_dtype, const CompactArgs &a, int blocks, hipStream_t stream);
+int launch_direct(int dk, int in_dtype, int rec_dtype, const DirectArgs &a, int blocks, hipStream_t stream);  // kvb_direct.hip
 
 }  // namespace kvb_impl
 #endif  // KVB_DEVICE_H

@@ -1,4 +1,5 @@
-// kvb_direct: kvb_direct_mfma_kernel (bf16, d = 128) and kvb_direct_kernel (other types and head sizes).
+// kvb_direct: kvb_direct_mfma_kernel, kvb_direct_mfma_long_kernel (16-bit inputs, d = 128) and kvb_direct_kernel
+// (fp32 inputs and the other head sizes).
 #include "kvb_device.h"
 
 namespace kvb_impl {
@@ -9,7 +10,7 @@ namespace kvb_impl {
 //   u_i = beta_i ( v_i - sum_{l<i} cK[i][l] u_l )       (row i of A Diag(beta) V)
 //   o_i = scale * sum_{l<=i} cQ[i][l] u_l
 // ---------------------------------------------------------------------------
-template <int D, typename TIn, bool PAGED>
+template <int D, typename TIn, typename TRec, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 {
     constexpr int LM = 64;   // longest context of this kernel
@@ -45,6 +46,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
     const TIn *qin = static_cast<const TIn *>(a.q);
     const TIn *kin = static_cast<const TIn *>(a.k);
     const TIn *vin = static_cast<const TIn *>(a.v);
+    const Out<TIn> out{a.out, a.out_wide != 0};
 
     for (int idx = tid; idx < L * D; idx += NT) {
         const int i = idx / D, e = idx % D;
@@ -88,11 +90,13 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
                 acc = fmaf(-cK[i][l], ul, acc);
                 o = fmaf(cQ[i][l], ul, o);
             }
-            const float ui = sB[i] * acc;
+            // the record as it is stored is what every later use reads
+            const TRec ur_i = from_f32<TRec>(sB[i] * acc);
+            const float ui = to_f32(ur_i);
             sU[i][tid] = ui;
             o = fmaf(cQ[i][i], ui, o);
-            a.out[row * D + tid] = a.scale * o;
-            a.st.buf_u[ru(i) * D + tid] = ui;
+            out.put1(row * D + tid, a.scale * o);
+            static_cast<TRec *>(a.st.buf_u)[ru(i) * D + tid] = ur_i;
         }
     }
     if (tid < L)
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// kvb_direct for bf16 inputs and d = 128, on the matrix cores throughout.
+// kvb_direct for 16-bit inputs (bf16 or fp16) and d = 128, on the matrix cores throughout.
 //
 // The context is cut into blocks of 16 rows.  With N_il = beta_i Gamma_il (k_i.k_l) (l < i)
 // and M_il = Gamma_il (q_i.k_l) (l <= i) the parallel form (Eq. 13) is
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 // solved block row by block row:  U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),
 // T_d = (I + N_dd)^-1 by blocked inversion (unit_lower_inverse16 below; N_dd is strictly lower),
 // O_d = sum_{e<=d} M_de U_e.
-//   * Gram tiles (k.k, q.k over dk = 128, bf16 operands): v_mfma_f32_16x16x32_bf16.
+//   * Gram tiles (k.k, q.k over dk = 128, 16-bit operands): v_mfma_f32_16x16x32_{bf16,f16}.
 //   * everything after that has fp32 operands: v_mfma_f32_16x16x4_f32 (exact products).
 //
 // Register chaining.  Call "A-form" of a 16x16 matrix X the register layout in which lane l
@@ -188,21 +192,20 @@ constexpr uint32_t pack2(Ts... xs)
 // Raw Gram tile from rows staged in LDS (row stride GS bf16 elements): lane l reads row l%16
 // of the A-side block and of the B-side block at k = 8*(l/16) + 32*step.  acc[v] =
 // (A-side row 4*(l/16)+v) . (B-side row l%16), i.e. the A-form of the (B-block, A-block) tile.
-template <int GS>
-__device__ __forceinline__ f32x4_t gram16(const bf16_t *arow, const bf16_t *brow, int lq)
+template <typename TIn, int GS>
+__device__ __forceinline__ f32x4_t gram16(const TIn *arow, const TIn *brow, int lq)
 {
     f32x4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
         const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
         const uint4 bv = *reinterpret_cast<const uint4 *>(brow + 8 * lq + 32 * st);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                    __builtin_bit_cast(bf16x8_t, bv), c, 0, 0, 0);
+        c = mfma16x32<TIn>(av, bv, c);
     }
     return c;
 }
 
-template <bool PAGED>
+template <typename TIn, typename TRec, bool PAGED>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void kvb_direct_mfma_kernel(
     const DirectArgs a)
 {
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     __shared__ __attribute__((aligned(16))) float sG[LM];
     __shared__ __attribute__((aligned(16))) float sB[LM];
     __shared__ int sBlk[NW][MAX_BLOCKS];
-    bf16_t *sK = reinterpret_cast<bf16_t *>(region);
+    TIn *sK = reinterpret_cast<TIn *>(region);
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NLOW;
     float4(*tT)[64] = tM + NLOW;
@@ -255,9 +258,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
     auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
     auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
-    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
-    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
-    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const TIn *qin = static_cast<const TIn *>(a.q);
+    const TIn *kin = static_cast<const TIn *>(a.k);
+    const TIn *vin = static_cast<const TIn *>(a.v);
+    const Out<TIn> out{a.out, a.out_wide != 0};
     const int nb = (L + 15) / 16;
     auto tri = [](int d, int e) { return d * (d + 1) / 2 + e; };
 
@@ -267,9 +271,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     u32x4_t kst[NB];
     const int srow = tid / 16, sc8 = tid % 16;
     // (uniform 64-bit base + 32-bit per-lane offset keeps the address arithmetic out of the VGPRs)
-    const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
-    const bf16_t *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
-    const bf16_t *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
+    const TIn *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const TIn *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const TIn *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
     const uint32_t qk_stride = (uint32_t)a.Hk * D, v_stride = (uint32_t)a.Hv * D;
 #pragma unroll
     for (int p = 0; p < NB; ++p) {   // rows past the context re-read its last row (never used)
@@ -315,7 +319,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
             a.st.buf_G[ru(lane)] = gv;
     }
     // stage K, Q; the thread that loaded a piece of K also appends it to the buffer
-    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k);
+    TIn *kb = static_cast<TIn *>(a.st.buf_k);
 #pragma unroll
     for (int p = 0; p < NB; ++p) {
         if (p < nb) {   // uniform
@@ -331,7 +335,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     // (two bits per entry, packed: a table indexed by the wave number would live in scratch)
     f32x4_t gdiag = {0.f, 0.f, 0.f, 0.f};
     if (wave < nb)
-        gdiag = gram16<GS>(sK + (16 * wave + c16) * GS, sK + (16 * wave + c16) * GS, lq);
+        gdiag = gram16<TIn, GS>(sK + (16 * wave + c16) * GS, sK + (16 * wave + c16) * GS, lq);
     f32x4_t gsh[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
@@ -339,15 +343,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
         gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         if (d < nb) {   // uniform
             if (t < 6) {
-                gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
+                gsh[n] = gram16<TIn, GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
             } else if (n > 0) {   // t >= 6 implies n >= 1
-                const bf16_t *arow = sK + (16 * e + c16) * GS;
+                const TIn *arow = sK + (16 * e + c16) * GS;
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
                     const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
-                    gsh[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, qop[n > 0 ? n - 1 : 0][st]),
-                        gsh[n], 0, 0, 0);
+                    gsh[n] = mfma16x32<TIn>(av, __builtin_bit_cast(uint4, qop[n > 0 ? n - 1 : 0][st]), gsh[n]);
                 }
             }
         }
@@ -419,8 +421,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
     // column tile c of the wave holds columns 32 wave + 2 n + c (n = 0..15): a lane's two
     // tiles are adjacent columns, so v arrives as one 4-byte load and results leave as float2
     f32x4_t U[NB][2];
-    float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
-    float *up = a.st.buf_u;
+    const size_t outp = (((size_t)b * Lmax) * a.Hv + h) * D;
+    TRec *up = static_cast<TRec *>(a.st.buf_u);
 #pragma unroll
     for (int d = 0; d < NB; ++d) {
         if (d < nb) {   // uniform
@@ -429,8 +431,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
                 const float bi = sB[i];   // zero beyond the context
-                acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
-                acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
+                const float2 vv = unpack_pair<TIn>(v_raw[d][v]);
+                acc[0][v] = bi * vv.x;
+                acc[1][v] = bi * vv.y;
             }
             o[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             o[1] = o[0];
@@ -451,15 +454,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 U[d][c] = mm16(tt, acc[c], f32x4_t{0.f, 0.f, 0.f, 0.f});
+                if constexpr (sizeof(TRec) == 2) {   // later blocks and this block's outputs read the records as stored
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        U[d][c][v] = rounded_to<TRec>(U[d][c][v]);
+                }
                 o[c] = mm16(mm, U[d][c], o[c]);
             }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
                 if (i < L) {
-                    *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
-                        make_float2(a.scale * o[0][v], a.scale * o[1][v]);
-                    *reinterpret_cast<float2 *>(up + (ru(i) * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                    out.put2(outp + ((uint32_t)i * v_stride + col2), a.scale * o[0][v], a.scale * o[1][v]);
+                    store2(up + (ru(i) * D + col2), U[d][0][v], U[d][1][v]);
                 }
             }
         }
@@ -475,7 +482,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(5, 5))) void
 // blocks and 16 of the 64 off-diagonal k.k and q.k tiles; the query rows of a tile are fetched
 // one tile ahead; the tile region (80 tiles, 80 KB) again takes the place of the staged keys.
 // ---------------------------------------------------------------------------
-template <bool PAGED>
+template <typename TIn, typename TRec, bool PAGED>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void kvb_direct_mfma_long_kernel(
     const DirectArgs a)
 {
@@ -493,7 +500,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __shared__ __attribute__((aligned(16))) float sG[LM];
     __shared__ __attribute__((aligned(16))) float sB[LM];
     __shared__ int sBlk[NW][MAX_BLOCKS];
-    bf16_t *sK = reinterpret_cast<bf16_t *>(region);
+    TIn *sK = reinterpret_cast<TIn *>(region);
     float4(*tN)[64] = reinterpret_cast<float4(*)[64]>(region);
     float4(*tM)[64] = tN + NKK;
     float4(*tT)[64] = tM + NLOW;
@@ -526,9 +533,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[wave], lane, load_block_id<PAGED>(a.st, s, lane));
     auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
     auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
-    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
-    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
-    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
+    const TIn *qin = static_cast<const TIn *>(a.q);
+    const TIn *kin = static_cast<const TIn *>(a.k);
+    const TIn *vin = static_cast<const TIn *>(a.v);
+    const Out<TIn> out{a.out, a.out_wide != 0};
     const int nb = (L + 15) / 16;
     auto tri = [](int d, int e) { return d * (d + 1) / 2 + e; };    // slot of pair d >= e
     auto trn = [](int d, int e) { return d * (d - 1) / 2 + e; };    // slot of pair d > e
@@ -555,9 +563,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     const int srow = tid / 16, sc8 = tid % 16;
-    const bf16_t *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
-    const bf16_t *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
-    const bf16_t *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
+    const TIn *kbase = kin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const TIn *qbase = qin + ((size_t)b * Lmax * a.Hk + hk) * D;
+    const TIn *vbase = vin + ((size_t)b * Lmax * a.Hv + h) * D;
     const uint32_t qk_stride = (uint32_t)a.Hk * D, v_stride = (uint32_t)a.Hv * D;
     const int col2 = 32 * wave + 2 * c16;
 
@@ -593,7 +601,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         if (t0 < L)
             a.st.buf_G[ru(t0)] = gv;
     }
-    bf16_t *kb = static_cast<bf16_t *>(a.st.buf_k);
+    TIn *kb = static_cast<TIn *>(a.st.buf_k);
 #pragma unroll
     for (int p = 0; p < NB; ++p) {
         if (p < nb) {   // uniform
@@ -611,7 +619,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         const int d = wave + NW * x;
         gdiag[x] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         if (d < nb)
-            gdiag[x] = gram16<GS>(sK + (16 * d + c16) * GS, sK + (16 * d + c16) * GS, lq);
+            gdiag[x] = gram16<TIn, GS>(sK + (16 * d + c16) * GS, sK + (16 * d + c16) * GS, lq);
     }
     // query rows of a q.k tile, in the operand layout (row 16 d + c16, k = 8 lq + 32 step),
     // requested one tile ahead of their use
@@ -642,15 +650,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         gsh[n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         if (d < nb) {   // uniform
             if (!isq) {
-                gsh[n] = gram16<GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
+                gsh[n] = gram16<TIn, GS>(sK + (16 * e + c16) * GS, sK + (16 * d + c16) * GS, lq);
             } else {
-                const bf16_t *arow = sK + (16 * e + c16) * GS;
+                const TIn *arow = sK + (16 * e + c16) * GS;
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
                     const uint4 av = *reinterpret_cast<const uint4 *>(arow + 8 * lq + 32 * st);
-                    gsh[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, n % 2 == 0 ? qa[st] : qb[st]),
-                        gsh[n], 0, 0, 0);
+                    gsh[n] = mfma16x32<TIn>(av, __builtin_bit_cast(uint4, n % 2 == 0 ? qa[st] : qb[st]), gsh[n]);
                 }
             }
         }
@@ -721,8 +727,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
     // ---- block forward substitution and outputs, this wave's 32 columns ----------
     f32x4_t U[NB][2];
-    float *outp = a.out + (((size_t)b * Lmax) * a.Hv + h) * D;
-    float *up = a.st.buf_u;
+    const size_t outp = (((size_t)b * Lmax) * a.Hv + h) * D;
+    TRec *up = static_cast<TRec *>(a.st.buf_u);
 #pragma unroll
     for (int d = 0; d < NB; ++d) {
         if (d < nb) {   // uniform
@@ -731,8 +737,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
                 const float bi = sB[i];   // zero beyond the context
-                acc[0][v] = bi * __uint_as_float(v_raw[d][v] << 16);
-                acc[1][v] = bi * __uint_as_float(v_raw[d][v] & 0xFFFF0000u);
+                const float2 vv = unpack_pair<TIn>(v_raw[d][v]);
+                acc[0][v] = bi * vv.x;
+                acc[1][v] = bi * vv.y;
             }
             o[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             o[1] = o[0];
@@ -753,15 +760,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 U[d][c] = mm16(tt, acc[c], f32x4_t{0.f, 0.f, 0.f, 0.f});
+                if constexpr (sizeof(TRec) == 2) {   // later blocks and this block's outputs read the records as stored
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        U[d][c][v] = rounded_to<TRec>(U[d][c][v]);
+                }
                 o[c] = mm16(mm, U[d][c], o[c]);
             }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * d + 4 * lq + v;
                 if (i < L) {
-                    *reinterpret_cast<float2 *>(outp + ((uint32_t)i * v_stride + col2)) =
-                        make_float2(a.scale * o[0][v], a.scale * o[1][v]);
-                    *reinterpret_cast<float2 *>(up + (ru(i) * D + col2)) = make_float2(U[d][0][v], U[d][1][v]);
+                    out.put2(outp + ((uint32_t)i * v_stride + col2), a.scale * o[0][v], a.scale * o[1][v]);
+                    store2(up + (ru(i) * D + col2), U[d][0][v], U[d][1][v]);
                 }
             }
         }
@@ -773,24 +784,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
-int launch_direct(int dk, int in_dtype, const DirectArgs &a, int blocks, hipStream_t stream)
+int launch_direct(int dk, int in_dtype, int rec_dtype, const DirectArgs &a, int blocks, hipStream_t stream)
 {
-    if (dk == 128 && in_dtype == KVB_BF16) {
-        if (a.Lmax > 64) {   // 5 .. 8 blocks of 16 rows
-            if (a.st.block_table)
-                launch(kvb_direct_mfma_long_kernel<true>, blocks, stream, a);
+    if (dk == 128 && in_dtype != KVB_F32)
+        return dispatch_types16(in_dtype, rec_dtype, [&]<typename TIn, typename TRec>() {
+            if (a.Lmax > 64)   // 5 .. 8 blocks of 16 rows
+                LAUNCH_PAGED(blocks, stream, a, kvb_direct_mfma_long_kernel<TIn, TRec);
             else
-                launch(kvb_direct_mfma_long_kernel<false>, blocks, stream, a);
-        } else if (a.st.block_table) {
-            launch(kvb_direct_mfma_kernel<true>, blocks, stream, a);
-        } else {
-            launch(kvb_direct_mfma_kernel<false>, blocks, stream, a);
-        }
-        return KVB_OK;
-    }
+                LAUNCH_PAGED(blocks, stream, a, kvb_direct_mfma_kernel<TIn, TRec);
+        });
     if (a.Lmax > 64)   // the plain kernel holds a 64-token context in LDS
         return KVB_EUNSUPPORTED;
-    return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_direct_kernel<D, TIn); });
+    return dispatch(dk, in_dtype, rec_dtype, [&]<int D, typename TIn, typename TRec>() {
+        if constexpr (!(D == 128 && sizeof(TIn) == 2))
+            LAUNCH_PAGED(blocks, stream, a, kvb_direct_kernel<D, TIn, TRec);
+    });
 }
 
 }  // namespace kvb_impl

@@ -8,7 +8,7 @@ namespace kvb_impl {
 // The rank-m sum is accumulated apart from the state so that the state tile can
 // stay in flight until the very end.
 // ---------------------------------------------------------------------------
-template <int D, typename TIn, bool PAGED>
+template <int D, typename TIn, typename TRec, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 {
     constexpr int LPR = D / 4;
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
     auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
     const float *Gbuf = a.st.buf_G;
     const TIn *kb = static_cast<const TIn *>(a.st.buf_k);
-    const float *ub = a.st.buf_u;
+    const TRec *ub = static_cast<const TRec *>(a.st.buf_u);
     const float Glast = Gbuf[ru(m - 1)];
 
     // first record tile, then the state tile, so the tile's loads retire first
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
             const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
             if (l < m) {
                 kt[x] = expf(Glast - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
-                ut[x] = ub[ru(l) * D + e];
+                ut[x] = to_f32(ub[ru(l) * D + e]);
             } else {
                 kt[x] = 0.0f;
                 ut[x] = 0.0f;
@@ -119,16 +119,21 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// kvb_flush for bf16 keys and d = 128, on the matrix cores.
+// kvb_flush for 16-bit keys and d = 128, on the matrix cores.
 //
 // The rank-m update is the dense contraction K^T (Diag(Gamma) U), dk x m by m x dv.  The keys
-// are bf16 as stored, so they are exact operands of v_mfma_f32_16x16x32_bf16; the other factor
-// x = Gamma_l u_l is fp32 and is cut into three bf16 pieces x = x1 + x2 + x3 (8 significand
-// bits each, by masking and exact subtraction), so that k * x = k*x1 + k*x2 + k*x3 holds
-// exactly and the sum is accumulated in fp32 as before.  The bf16 instruction runs at 16 times
-// the rate of the fp32 matrix instruction, so the three products still come at about 5 times
-// that rate and 10 times the rate of plain vector-ALU FMAs, which is what bounds the
-// vector-ALU kernel above from 16 records on.
+// are bf16 or fp16 as stored, so they are exact operands of v_mfma_f32_16x16x32_{bf16,f16}; the
+// other factor x = Gamma_l u_l is fp32 (also when u_l itself is a 16-bit record: the decay
+// weight is not) and is cut into pieces of the keys' type, x = x1 + x2 (+ x3), each piece the
+// leading bits of what is left, taken off by an exact subtraction, so that k * x = sum k * x_p
+// holds to the last piece and the sum is accumulated in fp32 as before.  bf16 pieces carry 8
+// significand bits: three of them give all 24 bits of a fp32 record; two (16 bits, 2^-17
+// relative) are far below the 2^-9 rounding a bf16 record already carries.  fp16 pieces carry
+// 11 bits: two give 22 bits (2^-23 relative, the rounding of fp32 itself is 2^-24); a piece
+// below the fp16 range (6e-8) is dropped, an absolute error that small against delta values
+// of order one.  The 16-bit instruction runs at 16 times the rate of the fp32 matrix
+// instruction, so even three products come at about 5 times that rate and 10 times the rate
+// of plain vector-ALU FMAs, which is what bounds the vector-ALU kernel above from 16 records on.
 //
 // Operand layout (lane = 16 lq + lm): A holds A[lm][8 lq + j], B holds B[8 lq + j][lm],
 // j = 0..7, the result D[4 lq + v][lm], v = 0..3.  The contraction index is the record,
@@ -143,13 +148,15 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 // MULTI: more than one 32-record chunk (cap > 32); the sums then stay in registers across the
 // chunks, otherwise each row tile is finished and stored as soon as its six products are done.
 // ---------------------------------------------------------------------------
-template <bool MULTI, bool PAGED>
+template <typename TIn, typename TRec, bool MULTI, bool PAGED>
 // (register budgets: 3 workgroups per CU, 2 where the sums persist)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MULTI ? 2 : 3)))
 void kvb_flush_mfma_kernel(const FlushArgs a)
 {
     constexpr int D = 128;
     constexpr int CH = 32;   // records per chunk
+    // pieces of the fp32 factor (see above)
+    constexpr int NP = (__is_same(TIn, bf16_t) && sizeof(TRec) == 4) ? 3 : 2;
     __shared__ int sBlk[NW][MAX_BLOCKS];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;   // (a scalar)
@@ -184,15 +191,15 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
     auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
     auto rk = [&](int l) { return pg.row(l, a.Hk, hk); };
     const float *Gbuf = a.st.buf_G;
-    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k);
-    const float *ub = a.st.buf_u;
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k);
+    const TRec *ub = static_cast<const TRec *>(a.st.buf_u);
     const float Glast = Gbuf[ru(m - 1)];
     const int col2 = 32 * wave + 2 * lm;
 
     // records 32 c + 8 lq + j of chunk c as raw bits; an index past m is clamped to record 0
     // (finite values that meet a zero weight)
     uint4 kraw[8];
-    float2 uraw[8];
+    Raw2<TRec> uraw[8];
     float Graw[8];
     auto load_chunk = [&](int c) {
 #pragma unroll
@@ -200,7 +207,7 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
             const int l = CH * c + 8 * lq + j;
             const int lc = l < m ? l : 0;
             kraw[j] = *reinterpret_cast<const uint4 *>(kb + rk(lc) * D + 8 * lm);
-            uraw[j] = *reinterpret_cast<const float2 *>(ub + ru(lc) * D + col2);
+            uraw[j] = load_raw2(ub + ru(lc) * D + col2);
             Graw[j] = Gbuf[ru(lc)];
         }
     };
@@ -227,33 +234,42 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
         ticket = take_ticket(&a.st.fill[s]);
 
     // B operands of a chunk: piece p of Gamma_l u_l[col2 + t], 8 records to a lane
-    bf16x8_t bop[2][3];
+    uint4 bop[2][NP];
     auto build_b = [&](int c) {
         float w[8];
+        float2 uf[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < 8; ++j) {
             w[j] = CH * c + 8 * lq + j < m ? expf(Glast - Graw[j]) : 0.0f;
+            uf[j] = unpack2r(uraw[j]);
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             float r[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                r[j] = w[j] * (t ? uraw[j].y : uraw[j].x);
+                r[j] = w[j] * (t ? uf[j].y : uf[j].x);
 #pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                // the leading 8 significand bits of what is left; the rest is exact in fp32
-                uint32_t top[8];
+            for (int p = 0; p < NP; ++p) {
+                // the leading significand bits of what is left; the rest is exact in fp32
+                uint32_t top[8];   // the piece, in the upper half of the word
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    top[j] = __builtin_bit_cast(uint32_t, r[j]) & 0xFFFF0000u;
-                    r[j] -= __builtin_bit_cast(float, top[j]);
+                    if constexpr (__is_same(TIn, bf16_t)) {
+                        top[j] = __builtin_bit_cast(uint32_t, r[j]) & 0xFFFF0000u;
+                        r[j] -= __builtin_bit_cast(float, top[j]);
+                    } else {
+                        const f16_t hp = from_f32<f16_t>(r[j]);
+                        top[j] = (uint32_t)hp.bits << 16;
+                        r[j] -= to_f32(hp);
+                    }
                 }
                 uint4 w4;
                 w4.x = (top[0] >> 16) | top[1];
                 w4.y = (top[2] >> 16) | top[3];
                 w4.z = (top[4] >> 16) | top[5];
                 w4.w = (top[6] >> 16) | top[7];
-                bop[t][p] = __builtin_bit_cast(bf16x8_t, w4);
+                bop[t][p] = w4;
             }
         }
     };
@@ -270,14 +286,14 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
         w4.y = d[2] | (d[3] << 16);
         w4.z = d[4] | (d[5] << 16);
         w4.w = d[6] | (d[7] << 16);
-        return __builtin_bit_cast(bf16x8_t, w4);
+        return w4;
     };
     auto products = [&](int rt, f32x4_t &c0, f32x4_t &c1) {
-        const bf16x8_t aop = build_a(rt);
+        const uint4 aop = build_a(rt);
 #pragma unroll
-        for (int p = 2; p >= 0; --p) {   // smallest pieces first
-            c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[0][p], c0, 0, 0, 0);
-            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[1][p], c1, 0, 0, 0);
+        for (int p = NP - 1; p >= 0; --p) {   // smallest pieces first
+            c0 = mfma16x32<TIn>(aop, bop[0][p], c0);
+            c1 = mfma16x32<TIn>(aop, bop[1][p], c1);
         }
     };
     const float gam = expf(Glast);
@@ -333,7 +349,7 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
 // every thread carries the same element of all records, in order, so no two threads
 // touch the same word.
 // ---------------------------------------------------------------------------
-template <int D, typename TIn, bool PAGED>
+template <int D, typename TIn, typename TRec, bool PAGED>
 __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
 {
     __shared__ int sBlk[NW][MAX_BLOCKS];
@@ -361,7 +377,7 @@ __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
     const Pages<PAGED> pg = make_pages<PAGED>(a.st, s, a.cap, sBlk[tid / 64], tid % 64, load_block_id<PAGED>(a.st, s, tid % 64));
     auto ru = [&](int l) { return pg.row(l, a.Hv, h); };
     auto rk = [&](int l) { return pg.row(l, a.Hk, h / r); };
-    float *ub = a.st.buf_u;
+    TRec *ub = static_cast<TRec *>(a.st.buf_u);
     float *Gb = a.st.buf_G;
     TIn *kb = static_cast<TIn *>(a.st.buf_k);
     for (int j = 0; j < n; ++j) {
@@ -381,21 +397,25 @@ __global__ __launch_bounds__(NT) void kvb_compact_kernel(const CompactArgs a)
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
-int launch_flush(int dk, int in_dtype, const FlushArgs &a, int blocks, hipStream_t stream)
+int launch_flush(int dk, int in_dtype, int rec_dtype, const FlushArgs &a, int blocks, hipStream_t stream)
 {
-    if (dk == 128 && in_dtype == KVB_BF16) {   // the matrix-core kernel
-        if (a.cap <= 32)
-            LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<false);
-        else
-            LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<true);
-        return KVB_OK;
-    }
-    return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_flush_kernel<D, TIn); });
+    if (dk == 128 && in_dtype != KVB_F32)   // the matrix-core kernel
+        return dispatch_types16(in_dtype, rec_dtype, [&]<typename TIn, typename TRec>() {
+            if (a.cap <= 32)
+                LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false);
+            else
+                LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true);
+        });
+    return dispatch(dk, in_dtype, rec_dtype, [&]<int D, typename TIn, typename TRec>() {
+        if constexpr (!(D == 128 && sizeof(TIn) == 2))
+            LAUNCH_PAGED(blocks, stream, a, kvb_flush_kernel<D, TIn, TRec);
+    });
 }
 
-int launch_compact(int dk, int in_dtype, const CompactArgs &a, int blocks, hipStream_t stream)
+int launch_compact(int dk, int in_dtype, int rec_dtype, const CompactArgs &a, int blocks, hipStream_t stream)
 {
-    return dispatch(dk, in_dtype, [&]<int D, typename TIn>() { LAUNCH_PAGED(blocks, stream, a, kvb_compact_kernel<D, TIn); });
+    return dispatch(dk, in_dtype, rec_dtype,
+                    [&]<int D, typename TIn, typename TRec>() { LAUNCH_PAGED(blocks, stream, a, kvb_compact_kernel<D, TIn, TRec); });
 }
 
 }  // namespace kvb_impl

@@ -1,11 +1,8 @@
-// kvb_step_kernel for bf16 inputs.
+// kvb_step_kernel for bf16 inputs, fp32 records.
 #include "kvb_step_kernel.h"
 
 namespace kvb_impl {
 
-int launch_step_bf16(int dk, const StepArgs &a, int blocks, hipStream_t stream)
-{
-    return launch_step_typed<bf16_t>(dk, a, blocks, stream);
-}
+template int launch_step_typed<bf16_t, float>(int dk, const StepArgs &a, int blocks, hipStream_t stream);
 
 }  // namespace kvb_impl

@@ -37,7 +37,7 @@ __device__ __forceinline__ float group_sum(float x)
 // workgroup applies the deferred update S <- gamma_f S0 + sum_{l<=f} Gamma_fl k_l^T u_l to
 // the state tile it already holds in registers and writes it back, which saves the second
 // kernel's re-read of the state.
-template <int D, typename TIn, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
+template <int D, typename TIn, typename TRec, int TM, int WREC, bool HAS_STATE, bool FUSE, bool STREAM, bool PAGED>
 // (register budget: the 64-record decode variants sit at the edge of three workgroups per CU; hold them there)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(TM == 1 && WREC == 64 && HAS_STATE ? 3 : 1)))
 void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg,
@@ -96,7 +96,8 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
     const TIn *vin = static_cast<const TIn *>(a.v);
     const float *Gbuf = a.st.buf_G;                              // record l of this head: Gbuf[ru(l)]
     const TIn *kb = static_cast<const TIn *>(a.st.buf_k);        //                        kb + rk(l) * D
-    const float4 *up = reinterpret_cast<const float4 *>(a.st.buf_u);   //                  up + ru(l) * LPR
+    const TRec *ub = static_cast<const TRec *>(a.st.buf_u);      //                        ub + ru(l) * D
+    const Out<TIn> out{a.out, a.out_wide != 0};
     const int blk_id = load_block_id<PAGED>(a.st, s, tid % 64);
 
     // ---- 1. loads that need only the request index --------------------------
@@ -202,11 +203,11 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
         kl_raw[p] = load_raw8(kb + rk(lc) * D + 8 * sub);
         Gl[p] = Gbuf[ru(lc)];
     }
-    float4 ur[UP];
+    Raw4<TRec> ur_raw[UP];
 #pragma unroll
     for (int j = 0; j < UP; ++j) {
         const int l = rg + RPP * j;
-        ur[j] = up[ru(l < f ? l : 0) * LPR + c4];
+        ur_raw[j] = load_raw4(ub + ru(l < f ? l : 0) * D + 4 * c4);
     }
     if constexpr (HAS_STATE && !EARLY)
         issue_state();
@@ -410,9 +411,11 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
     __syncthreads();
 
     // ---- 4. accumulate over buffered records and state rows ----------------
+    float4 ur[UP];
 #pragma unroll
     for (int j = 0; j < UP; ++j) {
         const int l = rg + RPP * j;
+        ur[j] = unpack4(ur_raw[j]);
         if (l < f) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -429,12 +432,16 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
 #pragma unroll
         for (int x0 = 0; x0 < UT; x0 += 4) {
             if ((UP + x0) * RPP < f) {   // uniform
-                float4 ut[4];
+                Raw4<TRec> ut_raw[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int l = (UP + x0 + j) * RPP + rg;
-                    ut[j] = up[ru(l < f ? l : 0) * LPR + c4];
+                    ut_raw[j] = load_raw4(ub + ru(l < f ? l : 0) * D + 4 * c4);
                 }
+                float4 ut[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    ut[j] = unpack4(ut_raw[j]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int l = (UP + x0 + j) * RPP + rg;
@@ -515,7 +522,9 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
                 for (int j = 0; j < TM; ++j)
                     if (j < i)
                         acc = fmaf(-cK[i][f + j], uprev[j], acc);
-                const float ui = bet[i] * acc;
+                // the record as it is stored is what every later use reads, this token's output included
+                const TRec ur_i = from_f32<TRec>(bet[i] * acc);
+                const float ui = to_f32(ur_i);
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
                     if (j < i)
@@ -523,8 +532,8 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
                 ao = fmaf(cQ[i][f + i], ui, ao);
                 uprev[i] = ui;
                 u_new = ui;
-                a.out[row * D + tid] = a.scale * ao;
-                a.st.buf_u[ru(f + i) * D + tid] = ui;
+                out.put1(row * D + tid, a.scale * ao);
+                static_cast<TRec *>(a.st.buf_u)[ru(f + i) * D + tid] = ur_i;
             }
         }
     }
@@ -549,7 +558,6 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
             for (int p = 0; p < NPASS; ++p) {
                 sreg[p].x *= gam; sreg[p].y *= gam; sreg[p].z *= gam; sreg[p].w *= gam;
             }
-            const float *ub = a.st.buf_u;
             // one LDS tile of LT records: record f itself comes from this workgroup's registers
             auto inject_new = [&](int l0) {
                 if (f >= l0 && f < l0 + LT) {
@@ -613,8 +621,7 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
                 int lr = min(l_done + grp, lmax);
                 size_t rowr = ru(lr);
                 Raw8<TIn> kq = load_raw8(kb + rk(lr) * D + 8 * sub);
-                float4 uq0 = up[rowr * LPR + 2 * sub];
-                float4 uq1 = up[rowr * LPR + 2 * sub + 1];
+                Raw8<TRec> uq = load_raw8(ub + rowr * D + 8 * sub);
                 float Gq = Gbuf[rowr];
                 for (int l0 = l_done; l0 < m; l0 += LT) {
                     __syncthreads();
@@ -629,18 +636,19 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
                         // (component by component: a select between two float4 objects is compiled
                         // as a select between their addresses, which puts them in scratch memory)
                         const bool in = l < f;
+                        float ux[8];
+                        unpack8(uq, ux);
                         *reinterpret_cast<float4 *>(&uu[grp][8 * sub]) = make_float4(
-                            in ? uq0.x : 0.0f, in ? uq0.y : 0.0f, in ? uq0.z : 0.0f, in ? uq0.w : 0.0f);
+                            in ? ux[0] : 0.0f, in ? ux[1] : 0.0f, in ? ux[2] : 0.0f, in ? ux[3] : 0.0f);
                         *reinterpret_cast<float4 *>(&uu[grp][8 * sub + 4]) = make_float4(
-                            in ? uq1.x : 0.0f, in ? uq1.y : 0.0f, in ? uq1.z : 0.0f, in ? uq1.w : 0.0f);
+                            in ? ux[4] : 0.0f, in ? ux[5] : 0.0f, in ? ux[6] : 0.0f, in ? ux[7] : 0.0f);
                     }
                     inject_new(l0);
                     // (the request past the last tile re-reads a valid record and is dropped)
                     lr = min(l0 + LT + grp, lmax);
                     rowr = ru(lr);
                     kq = load_raw8(kb + rk(lr) * D + 8 * sub);
-                    uq0 = up[rowr * LPR + 2 * sub];
-                    uq1 = up[rowr * LPR + 2 * sub + 1];
+                    uq = load_raw8(ub + rowr * D + 8 * sub);
                     Gq = Gbuf[rowr];
                     __syncthreads();
                     apply_tile(l0);
@@ -655,7 +663,7 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
                         const int idx = tid + NT * x, l = l0 + idx / D, e = idx % D;
                         if (l < f) {
                             kh[idx / D][e] = expf(Gc[0] - Gbuf[ru(l)]) * to_f32(kb[rk(l) * D + e]);
-                            uu[idx / D][e] = ub[ru(l) * D + e];
+                            uu[idx / D][e] = to_f32(ub[ru(l) * D + e]);
                         } else if (l > f) {
                             kh[idx / D][e] = 0.0f;
                             uu[idx / D][e] = 0.0f;
@@ -688,66 +696,85 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
             launch(__VA_ARGS__, false>, blocks, stream, (a).slot, (a).Hv, blocks, a);  \
     } while (0)
 
-template <int D, typename TIn, int TM, int WREC>
+template <int D, typename TIn, typename TRec, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
     // (a branch inside the kernel around the state loads would make the compiler's wait
     // counters conservative at the join, so these are compile-time variants)
-    const bool st = a.stream_state != 0;
+    const bool st = a.stream_state != 0 && D == 128;   // the small head sizes are not tuned: no streaming variant
     if constexpr (TM == 1) {
         if (a.threshold > 0) {
-            if (st)
-                LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, true);
-            else
-                LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, 1, WREC, true, true, false);
+            if constexpr (D == 128) {
+                if (st) {
+                    LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, true);
+                    return;
+                }
+            }
+            LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, false);
             return;
         }
     }
-    if (!a.st.state)
-        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, false, false, false);
-    else if (st)
-        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, true);
-    else
-        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TM, WREC, true, false, false);
+    if (!a.st.state) {
+        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, false, false, false);
+        return;
+    }
+    if constexpr (D == 128) {
+        if (st) {
+            LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, true);
+            return;
+        }
+    }
+    LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, false);
 }
 
-template <int D, typename TIn, int TM>
+template <int D, typename TIn, typename TRec, int TM>
 void launch_step_w(const StepArgs &a, int blocks, hipStream_t stream)
 {
     // Register window of buffered records.  For d = 128 the smallest tier that holds the
     // whole buffer is used; the smaller head sizes only carry the general (64 + tail) tier.
-    if (D == 128 && a.cap <= 16)
-        launch_step_s<D, TIn, TM, D == 128 ? 16 : 64>(a, blocks, stream);
-    else if (D == 128 && a.cap <= 32)
-        launch_step_s<D, TIn, TM, D == 128 ? 32 : 64>(a, blocks, stream);
-    else
-        launch_step_s<D, TIn, TM, 64>(a, blocks, stream);
+    if constexpr (D == 128) {
+        if (a.cap <= 16) {
+            launch_step_s<D, TIn, TRec, TM, 16>(a, blocks, stream);
+            return;
+        }
+        if (a.cap <= 32) {
+            launch_step_s<D, TIn, TRec, TM, 32>(a, blocks, stream);
+            return;
+        }
+    }
+    launch_step_s<D, TIn, TRec, TM, 64>(a, blocks, stream);
 }
 
-template <int D, typename TIn>
+template <int D, typename TIn, typename TRec>
 void launch_step_t(const StepArgs &a, int blocks, hipStream_t stream)
 {
-    if (a.T == 1)
-        launch_step_w<D, TIn, 1>(a, blocks, stream);
-    else if (a.T <= 4)
-        launch_step_w<D, TIn, 4>(a, blocks, stream);
-    else
-        launch_step_w<D, TIn, 8>(a, blocks, stream);
+    if (a.T == 1) {
+        launch_step_w<D, TIn, TRec, 1>(a, blocks, stream);
+        return;
+    }
+    // several drafts with 16-bit inputs and d = 128 belong to kvb_verify_mfma_kernel; the
+    // vector-ALU variants are not compiled for that pair
+    if constexpr (!(D == 128 && sizeof(TIn) == 2)) {
+        if (a.T <= 4)
+            launch_step_w<D, TIn, TRec, 4>(a, blocks, stream);
+        else
+            launch_step_w<D, TIn, TRec, 8>(a, blocks, stream);
+    }
 }
 
-// All head sizes of one input type.
-template <typename TIn>
+// All head sizes of one (input type, record type) pair.
+template <typename TIn, typename TRec>
 int launch_step_typed(int dk, const StepArgs &a, int blocks, hipStream_t stream)
 {
     switch (dk) {
     case 32:
-        launch_step_t<32, TIn>(a, blocks, stream);
+        launch_step_t<32, TIn, TRec>(a, blocks, stream);
         return KVB_OK;
     case 64:
-        launch_step_t<64, TIn>(a, blocks, stream);
+        launch_step_t<64, TIn, TRec>(a, blocks, stream);
         return KVB_OK;
     case 128:
-        launch_step_t<128, TIn>(a, blocks, stream);
+        launch_step_t<128, TIn, TRec>(a, blocks, stream);
         return KVB_OK;
     }
     return KVB_EUNSUPPORTED;

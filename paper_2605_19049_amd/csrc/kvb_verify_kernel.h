@@ -1,14 +1,18 @@
-// kvb_verify_mfma_kernel: kvb_verify / kvb_verify_tree for bf16 inputs and d = 128.
+// kvb_verify_mfma_kernel: kvb_verify / kvb_verify_tree for 16-bit inputs and d = 128.  Template code
+// only; kvb_verify_bf16.hip and kvb_verify_f16.hip instantiate it for their input type.
+#ifndef KVB_VERIFY_KERNEL_H
+#define KVB_VERIFY_KERNEL_H
+
 #include "kvb_device.h"
 
 namespace kvb_impl {
 
 // ---------------------------------------------------------------------------
-// kvb_verify for bf16 inputs and d = 128, on the matrix cores.
+// kvb_verify for 16-bit inputs (bf16 or fp16) and d = 128, on the matrix cores.
 //
 // With T drafts the step is a pair of small dense contractions (Sec. 3.3, Eq. 7; Eq. 15):
-//   stage 1   C1[m][l] = W[m] . k_l        W = [k_0..k_7 ; q_0..q_7] (16 x dk, bf16),
-//             l over the buffered and the new keys  -> v_mfma_f32_16x16x32_bf16
+//   stage 1   C1[m][l] = W[m] . k_l        W = [k_0..k_7 ; q_0..q_7] (16 x dk, 16-bit),
+//             l over the buffered and the new keys  -> v_mfma_f32_16x16x32_{bf16,f16}
 //   stage 2   acc[m][:] = sum_rows sW[row][m] S0[row][:] + sum_{l<f} cW[l][m] u_l[:]
 //             (16 x (dk + f)) . ((dk + f) x dv), fp32 operands -> v_mfma_f32_16x16x4_f32
 // where sW[row][m] = -gamma_i k_i[row] (m = i) or gamma_i q_i[row] (m = 8 + i) and
@@ -18,7 +22,7 @@ namespace kvb_impl {
 // one 128-byte line per row).  MFMA layouts: see kvb_direct_mfma_kernel; for 16x16x4 fp32
 // lane l supplies A[l%16][l/16] and B[l/16][l%16] and receives C[4*(l/16)+v][l%16].
 // ---------------------------------------------------------------------------
-template <int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
+template <typename TIn, typename TRec, int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
 // (register budgets: 4 waves per SIMD with a record window of 16 or 32, 3 with the 64-record window)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(!HAS_STATE ? 1 : WREC <= 32 ? 4 : 3)))
 void kvb_verify_mfma_kernel(const StepArgs a)
@@ -51,12 +55,13 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     if (s < 0 || s >= a.st.n_slots)
         return;
     const size_t unit = (size_t)s * a.Hv + h;
-    const bf16_t *qin = static_cast<const bf16_t *>(a.q);
-    const bf16_t *kin = static_cast<const bf16_t *>(a.k);
-    const bf16_t *vin = static_cast<const bf16_t *>(a.v);
-    const float *Gbuf = a.st.buf_G;                               // record l of this head: Gbuf[ru(l)]
-    const bf16_t *kb = static_cast<const bf16_t *>(a.st.buf_k);   //                        kb + rk(l) * D
-    const float *ub = a.st.buf_u;                                 //                        ub + ru(l) * D
+    const TIn *qin = static_cast<const TIn *>(a.q);
+    const TIn *kin = static_cast<const TIn *>(a.k);
+    const TIn *vin = static_cast<const TIn *>(a.v);
+    const float *Gbuf = a.st.buf_G;                          // record l of this head: Gbuf[ru(l)]
+    const TIn *kb = static_cast<const TIn *>(a.st.buf_k);    //                        kb + rk(l) * D
+    const TRec *ub = static_cast<const TRec *>(a.st.buf_u);  //                        ub + ru(l) * D
+    const Out<TIn> out{a.out, a.out_wide != 0};
     const int blk_id = load_block_id<PAGED>(a.st, s, lane);
 
     const int lm = lane % 16, lq = lane / 16;   // MFMA row/column index and k index of this lane
@@ -65,7 +70,7 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     // ---- 1. loads that need only the request index: raw bits, clamped addresses, no branches
     // row lm of W (draft lm % 8; k for lm < 8, q above), k-chunk lq of each 32-wide step
     const int wi = min(lm % 8, T - 1);
-    const bf16_t *wrow = (lm < 8 ? kin : qin) + (((size_t)b * T + wi) * a.Hk + hk) * D + 8 * lq;
+    const TIn *wrow = (lm < 8 ? kin : qin) + (((size_t)b * T + wi) * a.Hk + hk) * D + 8 * lq;
     uint4 wa[4];
 #pragma unroll
     for (int st = 0; st < 4; ++st)
@@ -129,8 +134,8 @@ void kvb_verify_mfma_kernel(const StepArgs a)
 #pragma unroll
     for (int x = 0; x < NTW; ++x) {
         const int n = 16 * (wave + NW * x) + lm;
-        const bf16_t *kp = n < f ? kb + rk(n) * D
-                                 : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
+        const TIn *kp = n < f ? kb + rk(n) * D
+                              : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
         Gn[x] = Gbuf[ru(n < f ? n : 0)];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -138,15 +143,15 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     }
     // buffered delta values: quad sq = records 4 sq .. 4 sq + 3, this lane: record 4 sq + lq,
     // columns 32 wave + 2 lm, + 1
-    float2 uq[WQ];
+    Raw2<TRec> uq[WQ];
 #pragma unroll
     for (int sq = 0; sq < WQ; ++sq) {
         const int l = 4 * sq + lq;
-        uq[sq] = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
+        uq[sq] = load_raw2(ub + ru(l < f ? l : 0) * D + col2);
     }
     // v of this wave's columns (used by lanes 0..31 in the last stage)
     const int colf = 32 * wave + lane % 32;
-    bf16_t v_raw[TMX];
+    TIn v_raw[TMX];
 #pragma unroll
     for (int i = 0; i < TMX; ++i)
         v_raw[i] = vin[(((size_t)b * T + min(i, T - 1)) * a.Hv + h) * D + colf];
@@ -221,11 +226,11 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     {
         // the chunk this lane holds for step == wave covers state rows 32 wave + 8 lq .. + 7
         float x[8];
-        unpack8(Raw8<bf16_t>{wa[0]}, x);
+        unpack8(Raw8<TIn>{wa[0]}, x);
 #pragma unroll
         for (int st = 1; st < 4; ++st) {
             float y[8];
-            unpack8(Raw8<bf16_t>{wa[st]}, y);
+            unpack8(Raw8<TIn>{wa[st]}, y);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 x[e] = wave == st ? y[e] : x[e];
@@ -279,8 +284,7 @@ void kvb_verify_mfma_kernel(const StepArgs a)
         f32x4_t c1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int st = 0; st < 4; ++st)
-            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[st]),
-                                                         __builtin_bit_cast(bf16x8_t, kk[st]), c1, 0, 0, 0);
+            c1 = mfma16x32<TIn>(wa[st], kk[st], c1);
         // this lane: rows m = 4 lq + v of W against key n
         const int n = 16 * tile + lm;
         float o[4];
@@ -304,8 +308,8 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     }
     for (int tile = wave + NW * NTW; TAIL && tile < ntile; tile += NW) {   // keys beyond the register window
         const int n = 16 * tile + lm;
-        const bf16_t *kp = n < f ? kb + rk(min(n, cap - 1)) * D
-                                 : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
+        const TIn *kp = n < f ? kb + rk(min(n, cap - 1)) * D
+                              : kin + (((size_t)b * T + min(max(n - f, 0), T - 1)) * a.Hk + hk) * D;
         uint4 kk[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -322,18 +326,23 @@ void kvb_verify_mfma_kernel(const StepArgs a)
         if (sq < nquad) {   // uniform
             const bool ok = 4 * sq + lq < f;
             const float aw = cW[4 * sq + lq][lm];
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uq[sq].x : 0.0f, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uq[sq].y : 0.0f, acc1, 0, 0, 0);
+            const float2 uv = unpack2r(uq[sq]);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uv.x : 0.0f, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, ok ? uv.y : 0.0f, acc1, 0, 0, 0);
         }
     }
     // records beyond the register window: four quads to a round trip (requested together, clamped)
     for (int s0 = WQ; TAIL && s0 < nquad; s0 += 4) {
-        float2 u4[4];
+        Raw2<TRec> u4r[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int l = 4 * (s0 + j) + lq;
-            u4[j] = *reinterpret_cast<const float2 *>(ub + ru(l < f ? l : 0) * D + col2);
+            u4r[j] = load_raw2(ub + ru(l < f ? l : 0) * D + col2);
         }
+        float2 u4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            u4[j] = unpack2r(u4r[j]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int l = 4 * (s0 + j) + lq;   // < 4 * 35 + 4 = 144 rows of cW
@@ -400,7 +409,8 @@ void kvb_verify_mfma_kernel(const StepArgs a)
                         ao = fmaf(cq[i][j], uprev[j], ao);
                     }
                 }
-                const float ui = bet[i] * acc;
+                // the record as it will be stored is what every later use reads
+                const float ui = rounded_to<TRec>(bet[i] * acc);
                 ao = fmaf(cq[i][i], ui, ao);
                 uprev[i] = ui;
                 fin[i][colf] = ui;                 // a lane overwrites only what it has read itself
@@ -415,13 +425,15 @@ void kvb_verify_mfma_kernel(const StepArgs a)
         const bool is_u = rr < T;
         const int i = is_u ? rr : rr - T;
         const float4 val = *reinterpret_cast<const float4 *>(&fin[is_u ? i : 8 + i][4 * c4]);
-        float *dst = is_u ? a.st.buf_u + ru(f + i) * D : a.out + (((size_t)b * T + i) * a.Hv + h) * D;
-        *reinterpret_cast<float4 *>(dst + 4 * c4) = val;
+        if (is_u)   // (already rounded to the record type: the conversion is exact)
+            store4(static_cast<TRec *>(a.st.buf_u) + ru(f + i) * D + 4 * c4, val);
+        else
+            out.put4((((size_t)b * T + i) * a.Hv + h) * D + 4 * c4, val);
     }
     if (tid < T)
         a.st.buf_G[ru(f + tid)] = GcTid;
     if (h % r == 0 && wave == 0 && lm < T) {   // lanes holding k rows store them
-        bf16_t *kw = static_cast<bf16_t *>(a.st.buf_k) + rk(f + lm) * D + 8 * lq;
+        TIn *kw = static_cast<TIn *>(a.st.buf_k) + rk(f + lm) * D + 8 * lq;
 #pragma unroll
         for (int st = 0; st < 4; ++st)
             *reinterpret_cast<uint4 *>(kw + 32 * st) = wa[st];
@@ -431,26 +443,28 @@ void kvb_verify_mfma_kernel(const StepArgs a)
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
-template <int WREC>
+template <typename TIn, typename TRec, int WREC>
 void launch_verify_w(const StepArgs &a, int blocks, hipStream_t stream)
 {
     if (!a.st.state)
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, false, false);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, false, false);
     else if (a.stream_state)
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, true, true);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, true);
     else
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<WREC, true, false);
+        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, false);
 }
 
-void launch_verify_mfma(const StepArgs &a, int blocks, hipStream_t stream)
+template <typename TIn, typename TRec>
+void launch_verify_typed(const StepArgs &a, int blocks, hipStream_t stream)
 {
     // record window: a request that fits has fill <= cap - T
     if (a.cap - a.T <= 16)
-        launch_verify_w<16>(a, blocks, stream);
+        launch_verify_w<TIn, TRec, 16>(a, blocks, stream);
     else if (a.cap - a.T <= 32)
-        launch_verify_w<32>(a, blocks, stream);
+        launch_verify_w<TIn, TRec, 32>(a, blocks, stream);
     else
-        launch_verify_w<64>(a, blocks, stream);
+        launch_verify_w<TIn, TRec, 64>(a, blocks, stream);
 }
 
 }  // namespace kvb_impl
+#endif  // KVB_VERIFY_KERNEL_H

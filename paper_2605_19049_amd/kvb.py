@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvb.so")
 
 OK, EINVAL, EUNSUPPORTED, EHIP = 0, -1, -2, -3
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 MAX_CAP, MAX_DRAFTS, MAX_DIRECT_LEN = 128, 8, 128
 STATUS_OVERFLOW = 1
 STATUS_BADPATH = 2
@@ -26,7 +26,7 @@ EXPORTS = ("kvb_decode", "kvb_decode_flush", "kvb_flush", "kvb_verify", "kvb_ver
 class KvbShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hk", ctypes.c_int32), ("Hv", ctypes.c_int32),
                 ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("cap", ctypes.c_int32),
-                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32), ("rec_dtype", ctypes.c_int32),
                 ("scale", ctypes.c_float)]
 
 
@@ -98,8 +98,14 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def shape(B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, out_dtype=F32):
-    return KvbShape(B, Hk, Hv, dk, dv, cap, in_dtype, out_dtype, scale)
+def shape(B, Hk, Hv, dk, dv, cap, in_dtype, scale=1.0, out_dtype=F32, rec_dtype=F32):
+    return KvbShape(B, Hk, Hv, dk, dv, cap, in_dtype, out_dtype, rec_dtype, scale)
+
+
+def torch_dtype(code):
+    """The torch element type of a KVB_* type code (memory plumbing)."""
+    import torch
+    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[code]
 
 
 def store(state, buf_k, buf_u, buf_G, fill, status, n_slots, flags=0, block_table=None, block_size=0,
@@ -213,12 +219,13 @@ class DeviceStore:
     with PyTorch (memory plumbing only)."""
 
     def __init__(self, n_slots, Hk, Hv, dk, dv, cap, in_dtype, device="cuda", with_state=True,
-                 block_size=None, n_blocks=None, block_table=None):
+                 block_size=None, n_blocks=None, block_table=None, rec_dtype=F32):
         """block_size given: paged record buffers, pools of n_blocks blocks and a block table
         [n_slots, ceil(cap / block_size)] (block_table: an int array of that shape; default
         slot s takes the blocks s*mb .. s*mb+mb-1)."""
         import torch
-        kd = torch.bfloat16 if in_dtype == BF16 else torch.float32
+        kd = torch_dtype(in_dtype)
+        self.rec_dtype = rec_dtype
         self.n_slots, self.Hk, self.Hv, self.dk, self.dv, self.cap = n_slots, Hk, Hv, dk, dv, cap
         self.in_dtype = in_dtype
         self.state = torch.zeros((n_slots, Hv, dk, dv), dtype=torch.float32, device=device) \
@@ -236,7 +243,7 @@ class DeviceStore:
             self.block_table, self.max_blocks, self.n_blocks = None, 0, 0
             nb, per = n_slots, cap
         self.buf_k = torch.zeros((nb, Hk, per, dk), dtype=kd, device=device)
-        self.buf_u = torch.zeros((nb, Hv, per, dv), dtype=torch.float32, device=device)
+        self.buf_u = torch.zeros((nb, Hv, per, dv), dtype=torch_dtype(rec_dtype), device=device)
         self.buf_G = torch.zeros((nb, Hv, per), dtype=torch.float32, device=device)
         self.fill = torch.zeros((n_slots,), dtype=torch.int32, device=device)
         self.status = torch.zeros((n_slots,), dtype=torch.int32, device=device)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_error_strings():
-    assert kvb.version() == 110
+    assert kvb.version() == 120
     assert kvb.strerror(kvb.OK) == "ok"
     assert "invalid" in kvb.strerror(kvb.EINVAL)
     assert "unsupported" in kvb.strerror(kvb.EUNSUPPORTED)
@@ -34,7 +34,8 @@ def test_version_and_error_strings():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(kvb.KvbShape) == 9 * 4
+    assert ctypes.sizeof(kvb.KvbShape) == 10 * 4
+    assert kvb.KvbShape.rec_dtype.offset == 8 * 4 and kvb.KvbShape.scale.offset == 9 * 4
     assert kvb.KvbStore.n_slots.offset == 6 * 8 and kvb.KvbStore.flags.offset == 6 * 8 + 4
     assert kvb.KvbStore.block_table.offset == 7 * 8 and kvb.KvbStore.block_size.offset == 8 * 8
     assert kvb.KvbStore.n_blocks.offset == 8 * 8 + 8
@@ -64,7 +65,13 @@ GOOD = dict(B=2, Hk=2, Hv=4, dk=128, dv=128, cap=16, in_dtype=kvb.BF16)
     (dict(B=-1), kvb.EINVAL), (dict(Hk=0), kvb.EINVAL), (dict(Hk=3), kvb.EINVAL),
     (dict(cap=0), kvb.EINVAL), (dict(cap=129), kvb.EINVAL), (dict(dk=0), kvb.EINVAL),
     (dict(dk=96, dv=96), kvb.EUNSUPPORTED), (dict(dk=128, dv=64), kvb.EUNSUPPORTED),
-    (dict(in_dtype=2), kvb.EUNSUPPORTED), (dict(out_dtype=1), kvb.EUNSUPPORTED),
+    (dict(in_dtype=3), kvb.EUNSUPPORTED), (dict(out_dtype=3), kvb.EUNSUPPORTED), (dict(rec_dtype=3), kvb.EUNSUPPORTED),
+    # 16-bit records and outputs take the inputs' own 16-bit type
+    (dict(in_dtype=kvb.BF16, out_dtype=kvb.F16), kvb.EUNSUPPORTED),
+    (dict(in_dtype=kvb.BF16, rec_dtype=kvb.F16), kvb.EUNSUPPORTED),
+    (dict(in_dtype=kvb.F16, rec_dtype=kvb.BF16), kvb.EUNSUPPORTED),
+    (dict(in_dtype=kvb.F32, out_dtype=kvb.BF16), kvb.EUNSUPPORTED),
+    (dict(in_dtype=kvb.F32, rec_dtype=kvb.F16), kvb.EUNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected(bad, code):
     sh = kvb.shape(**{**GOOD, **bad})
