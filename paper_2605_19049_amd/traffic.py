@@ -41,6 +41,17 @@ class Layout:
 PAPER = Layout(r=1, in_bytes=2, u_bytes=2, G_bytes=2, out_bytes=2, gate_bytes=2)
 KVB = Layout()
 
+_BYTES = {"f32": 4, "bf16": 2, "f16": 2}
+
+
+def layout(in_dtype="bf16", rec_dtype="f32", out_dtype="f32", r=2, dk=128, dv=128):
+    """The layout of a kvb configuration: element types as the names of include/kvb.h's type
+    codes.  The gates g, beta and the buffered cumulative log decay G are fp32 in every
+    configuration; layout("f16", "f16", "f16") is the paper's storage regime (Sec. 4.1) in this
+    library's record format."""
+    return Layout(dk=dk, dv=dv, r=r, in_bytes=_BYTES[in_dtype], u_bytes=_BYTES[rec_dtype],
+                  out_bytes=_BYTES[out_dtype])
+
 
 def decode_rw(lay, fill, with_state=True):
     """(read, write) bytes per v-head of one kvb_decode at pre-append fill `fill`."""

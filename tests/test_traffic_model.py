@@ -54,3 +54,21 @@ def test_kvb_layout_numbers_used_by_the_bench():
     assert tr.KVB.record == 644
     assert tr.total(tr.flush_rw(tr.KVB, 16)) == 2 * 65536 + 16 * 644
     assert tr.total(tr.chunk_cycle_rw(tr.KVB, 16)) == pytest.approx(67212 + 644 * 7.5 + (131072 + 10304) / 16)
+
+
+def test_16bit_storage_regime_layout():
+    """fp16 (or bf16) inputs, records and outputs, two v-heads per qk-head, d = 128: a record is
+    128 B of shared key + 256 B of delta value + 4 B of G; with r = 1 and 2-byte gates and G it is
+    the layout of the paper's Table 2 (checked above through the same counter)."""
+    lay = tr.layout("f16", "f16", "f16")
+    assert lay.record == 128 + 256 + 4
+    assert lay.token_in == 2 * 128 + 256 + 8 and lay.token_out == 256 + 388
+    assert tr.layout("bf16", "f32", "f32") == tr.KVB and tr.KVB.record == 644
+    paper = tr.Layout(r=1, in_bytes=2, u_bytes=2, G_bytes=2, out_bytes=2, gate_bytes=2)
+    d, m = 128, 16
+    rd, wr = tr.chunk_cycle_rw(paper, m)
+    assert rd == pytest.approx(4 * (1 + 1 / m) * d * d + 2 * (m + 4) * d + m + 5)       # Table 2, Chunkwise
+    # the same regime in this library's format (fp32 gates and G, keys shared by two heads) moves
+    # fewer bytes per token than the table's single-head count, and 2-3 % fewer than fp32 records
+    assert tr.total(tr.fused_cycle_rw(lay, 16)) < rd + wr
+    assert 0.96 < tr.total(tr.fused_cycle_rw(lay, 16)) / tr.total(tr.fused_cycle_rw(tr.KVB, 16)) < 0.98
