@@ -176,6 +176,18 @@ __device__ __forceinline__ float2 unpack2r(const Raw2<T> &r) { return unpack_pai
 __device__ __forceinline__ void store2(float *p, float x, float y) { *reinterpret_cast<float2 *>(p) = make_float2(x, y); }
 template <typename T>
 __device__ __forceinline__ void store2(T *p, float x, float y) { *reinterpret_cast<uint32_t *>(p) = pack_pair<T>(x, y); }
+// The same as streaming (non-temporal) stores, for results that this kernel does not read again.
+__device__ __forceinline__ void store2_nt(float *p, float x, float y)
+{
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(v2f{x, y}, reinterpret_cast<v2f *>(p));
+}
+template <typename T>
+__device__ __forceinline__ void store2_nt(T *p, float x, float y)
+{
+    static_assert(sizeof(T) == 2, "a 16-bit storage type");
+    __builtin_nontemporal_store(pack_pair<T>(x, y), reinterpret_cast<uint32_t *>(p));
+}
 __device__ __forceinline__ void store4(float *p, const float4 &v) { *reinterpret_cast<float4 *>(p) = v; }
 template <typename T>
 __device__ __forceinline__ void store4(T *p, const float4 &v)
@@ -212,6 +224,17 @@ struct Out {
                 store2(static_cast<float *>(p) + i, x, y);
             else
                 store2(static_cast<TIn *>(p) + i, x, y);
+        }
+    }
+    __device__ __forceinline__ void put2_nt(size_t i, float x, float y) const
+    {
+        if constexpr (sizeof(TIn) == 4) {
+            store2_nt(static_cast<float *>(p) + i, x, y);
+        } else {
+            if (wide)
+                store2_nt(static_cast<float *>(p) + i, x, y);
+            else
+                store2_nt(static_cast<TIn *>(p) + i, x, y);
         }
     }
     __device__ __forceinline__ void put4(size_t i, const float4 &v) const
@@ -468,6 +491,17 @@ void launch(void (*kernel)(Params...), int blocks, hipStream_t stream, const Arg
             launch(__VA_ARGS__, true>, blocks, stream, a);            \
         else                                                          \
             launch(__VA_ARGS__, false>, blocks, stream, a);           \
+    } while (0)
+
+// The same for kernels that take (slot, Hv, grid size) as three plain leading arguments ahead of the
+// argument struct: the build preloads the first kernel-argument words into scalar registers at wave
+// launch, so the load of slot[b] -- the head of every dependent chain -- goes out at once.
+#define LAUNCH_LEAD(blocks, stream, a, ...)                                            \
+    do {                                                                               \
+        if ((a).st.block_table)                                                        \
+            launch(__VA_ARGS__, true>, blocks, stream, (a).slot, (a).Hv, blocks, a);   \
+        else                                                                           \
+            launch(__VA_ARGS__, false>, blocks, stream, (a).slot, (a).Hv, blocks, a);  \
     } while (0)
 
 // The compiled (input type, record type) pairs: fp32 records with any input type, 16-bit records

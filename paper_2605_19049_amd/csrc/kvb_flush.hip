@@ -151,8 +151,10 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 template <typename TIn, typename TRec, bool MULTI, bool PAGED>
 // (register budgets: 3 workgroups per CU, 2 where the sums persist)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MULTI ? 2 : 3)))
-void kvb_flush_mfma_kernel(const FlushArgs a)
+void kvb_flush_mfma_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg, const FlushArgs a)
 {
+    // (the three leading arguments repeat a.slot, a.Hv and the grid size: preloaded into scalar registers
+    // at wave launch, so that the load of slot[b] does not wait for the fetch of the argument block)
     constexpr int D = 128;
     constexpr int CH = 32;   // records per chunk
     // pieces of the fp32 factor (see above)
@@ -161,13 +163,14 @@ void kvb_flush_mfma_kernel(const FlushArgs a)
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;   // (a scalar)
     const int lm = lane % 16, lq = lane / 16;
-    const int lb = logical_block();
-    const int b = lb / a.Hv;
-    const int h = lb % a.Hv;
+    const int lb = logical_block(nblocks_arg);
+    const int b = lb / Hv_arg;
+    const int s = slot_arg[b];
+    __builtin_amdgcn_sched_barrier(0);   // nothing that needs the argument block goes above this load
+    const int h = lb % Hv_arg;
     const int hk = h / (a.Hv / a.Hk);
     const int cap = a.cap;
 
-    const int s = a.slot[b];
     if (s < 0 || s >= a.st.n_slots)
         return;
     const int f = a.st.fill[s] & FILL_MASK;
@@ -402,9 +405,9 @@ int launch_flush(int dk, int in_dtype, int rec_dtype, const FlushArgs &a, int bl
     if (dk == 128 && in_dtype != KVB_F32)   // the matrix-core kernel
         return dispatch_types16(in_dtype, rec_dtype, [&]<typename TIn, typename TRec>() {
             if (a.cap <= 32)
-                LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false);
+                LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false);
             else
-                LAUNCH_PAGED(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true);
+                LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true);
         });
     return dispatch(dk, in_dtype, rec_dtype, [&]<int D, typename TIn, typename TRec>() {
         if constexpr (!(D == 128 && sizeof(TIn) == 2))

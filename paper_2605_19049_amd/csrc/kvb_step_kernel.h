@@ -688,14 +688,6 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
 // ---------------------------------------------------------------------------
 // launch
 // ---------------------------------------------------------------------------
-#define LAUNCH_STEP(blocks, stream, a, ...)                                            \
-    do {                                                                               \
-        if ((a).st.block_table)                                                        \
-            launch(__VA_ARGS__, true>, blocks, stream, (a).slot, (a).Hv, blocks, a);   \
-        else                                                                           \
-            launch(__VA_ARGS__, false>, blocks, stream, (a).slot, (a).Hv, blocks, a);  \
-    } while (0)
-
 template <int D, typename TIn, typename TRec, int TM, int WREC>
 void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
 {
@@ -706,25 +698,25 @@ void launch_step_s(const StepArgs &a, int blocks, hipStream_t stream)
         if (a.threshold > 0) {
             if constexpr (D == 128) {
                 if (st) {
-                    LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, true);
+                    LAUNCH_LEAD(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, true);
                     return;
                 }
             }
-            LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, false);
+            LAUNCH_LEAD(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, 1, WREC, true, true, false);
             return;
         }
     }
     if (!a.st.state) {
-        LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, false, false, false);
+        LAUNCH_LEAD(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, false, false, false);
         return;
     }
     if constexpr (D == 128) {
         if (st) {
-            LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, true);
+            LAUNCH_LEAD(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, true);
             return;
         }
     }
-    LAUNCH_STEP(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, false);
+    LAUNCH_LEAD(blocks, stream, a, kvb_step_kernel<D, TIn, TRec, TM, WREC, true, false, false);
 }
 
 template <int D, typename TIn, typename TRec, int TM>

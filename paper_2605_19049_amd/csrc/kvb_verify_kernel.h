@@ -25,8 +25,10 @@ namespace kvb_impl {
 template <typename TIn, typename TRec, int WREC, bool HAS_STATE, bool STREAM, bool PAGED>
 // (register budgets: 4 waves per SIMD with a record window of 16 or 32, 3 with the 64-record window)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(!HAS_STATE ? 1 : WREC <= 32 ? 4 : 3)))
-void kvb_verify_mfma_kernel(const StepArgs a)
+void kvb_verify_mfma_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg, const StepArgs a)
 {
+    // (the three leading arguments repeat a.slot, a.Hv and the grid size: preloaded into scalar registers
+    // at wave launch, so that the load of slot[b] does not wait for the fetch of the argument block)
     constexpr int D = 128;
     constexpr int TMX = KVB_MAX_DRAFTS;                       // 8
     constexpr int NTILE = (KVB_MAX_CAP + TMX + 15) / 16;      // key tiles of 16 (9)
@@ -43,15 +45,16 @@ void kvb_verify_mfma_kernel(const StepArgs a)
     __shared__ float sGc[TAIL ? NW : 1][TMX];   // per-wave table for the keys beyond the register window
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;   // (a scalar)
-    const int lb = logical_block();
-    const int b = lb / a.Hv;
-    const int h = lb % a.Hv;
+    const int lb = logical_block(nblocks_arg);
+    const int b = lb / Hv_arg;
+    const int s = slot_arg[b];
+    __builtin_amdgcn_sched_barrier(0);   // nothing that needs the argument block goes above this load
+    const int h = lb % Hv_arg;
     const int r = a.Hv / a.Hk;
     const int hk = h / r;
     const int T = a.T;
     const int cap = a.cap;
 
-    const int s = a.slot[b];
     if (s < 0 || s >= a.st.n_slots)
         return;
     const size_t unit = (size_t)s * a.Hv + h;
@@ -447,11 +450,11 @@ template <typename TIn, typename TRec, int WREC>
 void launch_verify_w(const StepArgs &a, int blocks, hipStream_t stream)
 {
     if (!a.st.state)
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, false, false);
+        LAUNCH_LEAD(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, false, false);
     else if (a.stream_state)
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, true);
+        LAUNCH_LEAD(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, true);
     else
-        LAUNCH_PAGED(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, false);
+        LAUNCH_LEAD(blocks, stream, a, kvb_verify_mfma_kernel<TIn, TRec, WREC, true, false);
 }
 
 template <typename TIn, typename TRec>
