@@ -676,8 +676,15 @@ void kvb_step_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_ar
             }
             float4 *sw = reinterpret_cast<float4 *>(a.st.state + unit * D * D);
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p)
-                sw[(size_t)(rg + RPP * p) * LPR + c4] = sreg[p];
+            for (int p = 0; p < NPASS; ++p) {
+                if constexpr (STREAM) {   // a state that is streamed in is streamed out again (+1 % on 1 GiB of state)
+                    typedef float v4f __attribute__((ext_vector_type(4)));
+                    __builtin_nontemporal_store(v4f{sreg[p].x, sreg[p].y, sreg[p].z, sreg[p].w},
+                                                reinterpret_cast<v4f *>(sw + (size_t)(rg + RPP * p) * LPR + c4));
+                } else {
+                    sw[(size_t)(rg + RPP * p) * LPR + c4] = sreg[p];
+                }
+            }
             new_fill = 0;
         }
     }

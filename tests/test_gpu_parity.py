@@ -290,11 +290,15 @@ def test_spec_verify_tree_full():
 
 # --------------------------------------------------------------------------- direct
 def _direct_case(B, Hk, Hv, d, Lmax, cap, in_dtype, seed, lens=None, then_decode=True, block_size=None,
-                 scatter=False, rec_dtype="f32", out_dtype="f32"):
+                 scatter=False, rec_dtype="f32", out_dtype="f32", poison=False):
     rng = np.random.default_rng(seed)
     if lens is None:
         lens = synth.context_lengths(rng, B, 1, Lmax)
     tok = synth.token_stream(rng, B, Lmax, Hk, Hv, d, d, in_dtype)
+    if poison:   # whatever lies past a request's context must not reach its results
+        for b in range(B):
+            for x in tok.values():
+                x[b, lens[b]:] = np.nan
     lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, with_state=False, block_size=block_size,
                   rec_dtype=rec_dtype, out_dtype=out_dtype, **(_scattered(B, seed) if scatter else {}))
     lay.ds.fill.fill_(3)          # stale fill must be discarded
@@ -338,6 +342,17 @@ def test_direct_small(d, in_dtype, Lmax):
     e = _direct_case(B=5, Hk=2, Hv=4, d=d, Lmax=Lmax, cap=max(Lmax, 8), in_dtype=in_dtype, seed=50 + Lmax)
     say("direct d=%d %s Lmax=%d rel err out/u/decode/state: %.2e %.2e %.2e %.2e" % ((d, in_dtype, Lmax) + e))
     H.check(e, in_dtype)
+
+
+def test_direct_ignores_rows_beyond_the_context():
+    """q, k, v, g, beta rows past len[b] hold NaN: outputs, records and the folded state of the valid
+    rows are unaffected (every kernel of kvb_direct: 4 blocks, 8 blocks, the plain one)."""
+    for d, in_dtype, Lmax in ((128, "bf16", 64), (128, "bf16", 128), (128, "f16", 40), (32, "f32", 16)):
+        e = _direct_case(B=6, Hk=2, Hv=4, d=d, Lmax=Lmax, cap=Lmax, in_dtype=in_dtype, seed=70 + Lmax, poison=True,
+                         then_decode=False)
+        say("direct with NaN beyond the context, d=%d %s Lmax=%d: rel err out/u/decode/state %.2e %.2e %.2e %.2e"
+            % ((d, in_dtype, Lmax) + e))
+        H.check(e, in_dtype)
 
 
 def test_direct_len_zero_and_one():
