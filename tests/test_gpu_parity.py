@@ -485,6 +485,26 @@ def test_closed_forms_on_the_gpu():
     assert np.array_equal(S, S0)
 
 
+@pytest.mark.parametrize("B, Hk, Hv, C", [(2, 1, 2, 16), (3, 2, 4, 32), (40, 16, 32, 16), (2, 1, 2, 64)])
+def test_decode_ignores_whatever_lies_beyond_the_fill(B, Hk, Hv, C):
+    """The record buffers start out full of NaN: a record past the fill may be read (a small launch
+    requests the whole window before it knows the fill) but must never reach a result.  Small and
+    large launches (the latter wait for the fill), windows of 16, 32 and 64 records."""
+    rng = np.random.default_rng(74 + C)
+    d = 128
+    S0 = H.prefix_state(rng, B, Hk, Hv, d, d, "bf16", 4)
+    tok = synth.token_stream(rng, B, C + 5, Hk, Hv, d, d, "bf16")
+    for fused in (True, False):
+        lay = H.Layer(B, Hk, Hv, d, d, cap=C, in_dtype="bf16")
+        lay.ds.buf_u.fill_(float("nan"))
+        lay.ds.buf_k.fill_(float("nan"))
+        lay.ds.buf_G.fill_(float("nan"))
+        o, u, S, _ = H.run_decode(lay, S0, tok, C, fused=fused)
+        o_ref, u_ref, S_ref = oracle.kvb_decode_expected(S0, tok["q"], tok["k"], tok["v"], tok["g"], tok["beta"])
+        assert np.isfinite(o).all() and np.isfinite(S).all()
+        H.check((H.rel_err(o, o_ref), H.rel_err(u, u_ref), H.rel_err(S, S_ref)), "bf16")
+
+
 def test_strong_decay_neither_overflows_nor_underflows_to_nan():
     """g = -20 per token over a 64-record chunk: gamma ratios are never formed."""
     rng = np.random.default_rng(73)
