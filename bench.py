@@ -27,7 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
-TRAFFIC_FILE = "profiles/kvb_decode_flush_qwen3next_hbm_traffic.txt"
+TRAFFIC_FILE = "profiles/kvb_decode_flush_qwen3next_l2_fabric_traffic.txt"
 
 
 def parse():
@@ -242,20 +242,25 @@ def roofline_of(job, launches, fused, extra=None):
     return res
 
 
-def measured_traffic(workload, fused, types):
-    """Bytes that left the L2 caches per launch of the dominant kernel (towards the last-level
-    cache and HBM), as the rocprofv3 FETCH_SIZE / WRITE_SIZE counters measured them in the run
-    summarised under profiles/ -- a stored figure, not one of this run; None for configurations
-    that summary does not cover."""
-    if workload != "qwen3next_decode" or not fused or types != ("bf16", "f32", "f32"):
-        return None
+def measured_traffic(workload, fused, types, paged=False):
+    """{"traffic", "traffic_source"}: bytes that left the L2 caches per launch of the dominant
+    kernel (towards the last-level cache and HBM), as the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    counters measured them in the run summarised under profiles/ (warm and cold instance read
+    the same) -- a stored figure, not one of this run; None for configurations that summary
+    does not cover."""
+    none = {"traffic": None, "traffic_source": None}
+    if workload != "qwen3next_decode" or not fused or paged or types != ("bf16", "f32", "f32"):
+        return none
     try:
         for line in open(os.path.join(ROOT, TRAFFIC_FILE)):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+                return {"traffic": float(line.split("=")[1]),
+                        "traffic_source": TRAFFIC_FILE + " (static: rocprofv3 FETCH_SIZE/WRITE_SIZE of an earlier "
+                                          "run of this workload; bytes that crossed between the L2 caches and the "
+                                          "fabric, last-level-cache hits included)"}
     except OSError:
         pass
-    return None
+    return none
 
 
 # --------------------------------------------------------------------------- other entry points
@@ -577,9 +582,7 @@ def main():
                        "us_per_layer_step": per_layer_step * 1e6,
                        "host_wall_ms_per_step": wall / K * 1e3},
         "roofline": roofline_of(job, launches, fused, {
-            "traffic": measured_traffic(w.name, fused, types),
-            "traffic_source": TRAFFIC_FILE + " (static: rocprofv3 FETCH_SIZE/WRITE_SIZE of an earlier run of this "
-                              "workload; bytes that left the L2 caches, last-level-cache hits included)",
+            **measured_traffic(w.name, fused, types, paged=bool(args.block_size)),
             "footprint": "%.0f MiB of state re-read every step: %s the 256 MB last-level cache" % (
                 state_mib, "fits" if state_mib <= 256 else "exceeds")}),
     }
@@ -600,6 +603,7 @@ def main():
         cl = cold.kernel_times(2 * wc.C)
         cstep = statistics.median(csecs) / (Kc * wc.layers)
         res["roofline_cold"] = roofline_of(cold, cl, fused, {
+            **measured_traffic(w.name, fused, types, paged=bool(args.block_size)),
             "workload": "%s: %d MiB of state, state loads non-temporal" % (wc.name, 8 * state_mib),
             "graph_us_per_layer_step": cstep * 1e6,
             "graph_full_cycle_GBps": cold.cycle_bytes() / cstep / 1e9,
