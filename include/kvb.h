@@ -52,17 +52,27 @@ extern "C" {
 #define KVB_F32  0
 #define KVB_BF16 1
 #define KVB_F16  2
+/* Which (in_dtype, head size) pairs are tuned.  d = 128 with KVB_BF16 or KVB_F16 inputs (any
+ * allowed rec_dtype / out_dtype) is the pair the kernels are built and measured for: matrix-
+ * instruction kernels for kvb_verify, kvb_verify_tree, kvb_flush and kvb_direct, the streaming
+ * decode kernel for kvb_decode / kvb_decode_flush.  KVB_F32 inputs at any head size, and
+ * d = 32 or 64 with any input type, run plain vector-ALU kernels that exist for correctness
+ * (the fp32 parity workload, small test shapes): same results, no performance claim, and
+ * kvb_direct is limited to 64 tokens there. */
 
 #define KVB_MAX_CAP        128 /* largest `cap` (the paper buffers at most d records, Sec. 3.4) */
 #define KVB_MAX_DRAFTS       8 /* largest T of kvb_verify (Sec. 4.2 sweeps up to 8)             */
 #define KVB_MAX_DIRECT_LEN 128 /* largest Lmax of kvb_direct (Sec. 3.4: contexts up to d tokens);
-                                  bf16 inputs with d = 128; the other compiled pairs take 64     */
+                                  16-bit inputs with d = 128; the other compiled pairs take 64   */
 #define KVB_MAX_BLOCKS      16 /* longest block-table row (KVB_MAX_CAP / smallest block)        */
 
 /* kvb_store.flags: how the state should travel through the caches.  With neither bit the
- * library streams (non-temporal loads) when one call touches more state than the 256 MB
- * last-level cache holds.  A model with many GDN layers should set KVB_STORE_STREAM: each
- * layer's state is next read one token later, after every other layer's has passed through. */
+ * library streams (non-temporal loads, and non-temporal stores when the state is written
+ * back) when the states one call touches, 4 * B * Hv * dk * dv bytes, exceed 384 MiB: one and
+ * a half times the 256 MB last-level cache, because a state of 256 MiB that is re-read every
+ * step still finds most of itself there.  A model with many GDN layers should set
+ * KVB_STORE_STREAM: each layer's state is next read one token later, after every other
+ * layer's has passed through. */
 #define KVB_STORE_STREAM   1
 #define KVB_STORE_RESIDENT 2
 
@@ -225,10 +235,14 @@ int kvb_compact(const kvb_shape *shape, const kvb_store *store, const int32_t *s
  * with kvb_decode (state NULL), and kvb_flush on a zeroed state folds the
  * records into a state once the context outgrows the buffer.
  *   len   device int32 [B], 0..Lmax        Lmax 1..min(cap, KVB_MAX_DIRECT_LEN); above 64 only for
- *         bf16 inputs with d = 128 (KVB_EUNSUPPORTED otherwise)
+ *         16-bit inputs with d = 128 (KVB_EUNSUPPORTED otherwise)
  *   q, k  device [B, Lmax, Hk, dk]  v device [B, Lmax, Hv, dv]  g, beta device [B, Lmax, Hv]
  *   out   device [B, Lmax, Hv, dv] out_dtype; rows >= len[b] are not written
  * len[b] outside 0..Lmax is clamped to Lmax with KVB_STATUS_OVERFLOW.
+ * With a 16-bit rec_dtype the outputs read the records as stored (rounded), like everywhere
+ * else; the delta values themselves are solved for in fp32 before they are rounded -- all
+ * rows at once up to 64 tokens, 16 rows at a time above that -- so a row's delta value does
+ * not see the rounding of the rows solved with it.
  */
 int kvb_direct(const kvb_shape *shape, const kvb_store *store, const int32_t *slot,
                const int32_t *len, int32_t Lmax,
