@@ -66,17 +66,20 @@ int check_tokens(const void *q, const void *k, const void *v, const float *g, co
 }
 
 // Whether the state should be streamed past the caches: the caller's hint, else by this
-// call's own state footprint against the 256 MB last-level cache.  The switch sits at 1.5 times
-// the cache: a state of 256 MiB re-read every step still finds most of itself there and runs
-// faster with plain loads, one of 512 MiB does not.
-bool stream_state(const kvb_shape *sh, const kvb_store *st)
+// call's own state footprint against the 256 MB last-level cache.  For the calls that only read
+// the state the switch sits at 1.5 times the cache: a state of 256 MiB re-read every step still
+// finds most of itself there and runs faster with plain loads, one of 512 MiB does not.  kvb_flush
+// reads and writes the state, twice the lines through the cache: measured, streaming wins from
+// about 200 MiB of state on (16 records: 65 against 71 us at 192 MiB, 88 against 84 at 224 MiB;
+// 64 records: 139 against 107 us at 256 MiB), so its switch sits at 192 MiB.
+bool stream_state(const kvb_shape *sh, const kvb_store *st, double limit_mib = 384.0)
 {
     if (st->flags & KVB_STORE_STREAM)
         return true;
     if (st->flags & KVB_STORE_RESIDENT)
         return false;
     const double bytes = 4.0 * sh->B * sh->Hv * sh->dk * sh->dv;
-    return bytes > 384.0 * 1024 * 1024;
+    return bytes > limit_mib * 1024 * 1024;
 }
 
 Store dev_store(const kvb_store *st)
@@ -215,7 +218,8 @@ int kvb_flush(const kvb_shape *shape, const kvb_store *store, const int32_t *slo
         return KVB_EINVAL;
     if (shape->B == 0)
         return KVB_OK;
-    FlushArgs a{dev_store(store), slot, accepted, shape->Hk, shape->Hv, shape->cap, threshold};
+    FlushArgs a{dev_store(store), slot, accepted, shape->Hk, shape->Hv, shape->cap, threshold,
+                store->state && stream_state(shape, store, 192.0) ? 1 : 0};
     const int blocks = shape->B * shape->Hv;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     g_launch_status = hipSuccess;

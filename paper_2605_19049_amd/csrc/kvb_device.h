@@ -277,6 +277,19 @@ __device__ __forceinline__ float4 load_state4(const float4 *p)
     }
 }
 
+// The same for an 8-byte piece.
+template <bool STREAM>
+__device__ __forceinline__ float2 load_state2(const float *p)
+{
+    if constexpr (STREAM) {
+        typedef float v2f __attribute__((ext_vector_type(2)));
+        const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+        return make_float2(t.x, t.y);
+    } else {
+        return *reinterpret_cast<const float2 *>(p);
+    }
+}
+
 __device__ __forceinline__ void fma4(float4 &acc, float c, const float4 &x)
 {
     acc.x = fmaf(c, x.x, acc.x);
@@ -433,6 +446,7 @@ struct FlushArgs {
     const int32_t *slot;
     const int32_t *accepted;
     int32_t Hk, Hv, cap, threshold;
+    int32_t stream;   // non-temporal state loads and stores
 };
 
 struct DirectArgs {

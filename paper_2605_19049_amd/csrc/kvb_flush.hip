@@ -147,8 +147,13 @@ __global__ __launch_bounds__(NT) void kvb_flush_kernel(const FlushArgs a)
 // all rows and needs nothing from the other waves: the kernel has no barrier.
 // MULTI: more than one 32-record chunk (cap > 32); the sums then stay in registers across the
 // chunks, otherwise each row tile is finished and stored as soon as its six products are done.
+// STREAM: the state is read with non-temporal loads AND written back with non-temporal stores,
+// for a state too large to be found in the last-level cache at its next use.  Only the two
+// together pay: measured at 256 MiB of state and 64 records, 138 us with either or neither,
+// 107 us with both (a state that passes through the cache in one direction still turns it
+// over); at 128 MiB, which the cache keeps, they cost 10 %.
 // ---------------------------------------------------------------------------
-template <typename TIn, typename TRec, bool MULTI, bool PAGED>
+template <typename TIn, typename TRec, bool MULTI, bool STREAM, bool PAGED>
 // (register budgets: 3 workgroups per CU, 2 where the sums persist)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MULTI ? 2 : 3)))
 void kvb_flush_mfma_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblocks_arg, const FlushArgs a)
@@ -226,7 +231,7 @@ void kvb_flush_mfma_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblo
     auto issue_state = [&](int rt) {
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            sreg[rt % WIN][v] = *reinterpret_cast<const float2 *>(sp + (size_t)(32 * lq + 8 * v + rt) * D);
+            sreg[rt % WIN][v] = load_state2<STREAM>(sp + (size_t)(32 * lq + 8 * v + rt) * D);
         __builtin_amdgcn_sched_barrier(0);   // issue in the order they are consumed
     };
 #pragma unroll
@@ -306,7 +311,10 @@ void kvb_flush_mfma_kernel(const int32_t *slot_arg, int32_t Hv_arg, int32_t nblo
             float2 o;
             o.x = fmaf(gam, sreg[rt % WIN][v].x, c0[v]);
             o.y = fmaf(gam, sreg[rt % WIN][v].y, c1[v]);
-            *reinterpret_cast<float2 *>(sp + (size_t)(32 * lq + 8 * v + rt) * D) = o;
+            if constexpr (STREAM)
+                store2_nt(sp + (size_t)(32 * lq + 8 * v + rt) * D, o.x, o.y);
+            else
+                *reinterpret_cast<float2 *>(sp + (size_t)(32 * lq + 8 * v + rt) * D) = o;
         }
         if (rt + WIN < 8) {
             __builtin_amdgcn_sched_barrier(0);
@@ -404,10 +412,17 @@ int launch_flush(int dk, int in_dtype, int rec_dtype, const FlushArgs &a, int bl
 {
     if (dk == 128 && in_dtype != KVB_F32)   // the matrix-core kernel
         return dispatch_types16(in_dtype, rec_dtype, [&]<typename TIn, typename TRec>() {
-            if (a.cap <= 32)
-                LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false);
-            else
-                LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true);
+            if (a.cap <= 32) {
+                if (a.stream)
+                    LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false, true);
+                else
+                    LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, false, false);
+            } else {
+                if (a.stream)
+                    LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true, true);
+                else
+                    LAUNCH_LEAD(blocks, stream, a, kvb_flush_mfma_kernel<TIn, TRec, true, false);
+            }
         });
     return dispatch(dk, in_dtype, rec_dtype, [&]<int D, typename TIn, typename TRec>() {
         if constexpr (!(D == 128 && sizeof(TIn) == 2))
