@@ -801,6 +801,31 @@ def test_kv_only_verify_and_stream_hint_do_not_change_results():
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("in_dtype, rec_dtype, cap", [("bf16", "f32", 8), ("bf16", "f32", 40), ("f16", "f16", 40),
+                                                      ("bf16", "bf16", 16), ("f32", "f32", 12)])
+def test_stream_hint_does_not_change_kvb_flush(in_dtype, rec_dtype, cap):
+    """kvb_flush with the state streamed past the caches (non-temporal loads and stores, what the
+    library chooses by itself for large batches) against the default path, bit for bit."""
+    rng = np.random.default_rng(1200 + cap)
+    B, Hk, Hv, d = 3, 2, 4, 128
+    S0 = synth.random_state(rng, B, Hv, d, d)
+    tok = H.upload_tokens(synth.token_stream(rng, B, cap, Hk, Hv, d, d, in_dtype), in_dtype)
+    res = []
+    for flags in (kvb.STORE_RESIDENT, kvb.STORE_STREAM):
+        lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, rec_dtype=rec_dtype)
+        lay.set_state(S0)
+        out = lay.new_out(B, Hv, d)
+        for t in range(cap - 1):
+            kvb.kvb_decode(lay.shape(), lay.ds.c(flags=flags), lay.slot, *[H.step_view(tok, t)[n] for n in
+                           ("q", "k", "v", "g", "beta")], out)
+        kvb.kvb_flush(lay.shape(), lay.ds.c(flags=flags), lay.slot, None, 1)
+        torch.cuda.synchronize()
+        assert not lay.ds.fill[lay.slot.long()].any()
+        res.append(lay.get_state())
+    assert np.array_equal(res[0], res[1])
+    assert np.isfinite(res[0]).all() and not np.array_equal(res[0], np.asarray(S0, dtype=np.float32))
+
+
 # --------------------------------------------------------------------------- paged record buffers
 @pytest.mark.parametrize("d, in_dtype, C, block_size, fused", [
     (128, "bf16", 16, 16, True), (128, "bf16", 16, 8, True), (128, "bf16", 16, 8, False),
