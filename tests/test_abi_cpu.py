@@ -3,6 +3,7 @@ declares, and rejects bad arguments before touching the GPU (no compute calls he
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -154,3 +155,40 @@ def test_check_flag_raises():
     with pytest.raises(kvb.KvbError) as e:
         kvb.kvb_flush(sh, _store(), A, None, 1, stream=0)
     assert e.value.code == kvb.EINVAL
+
+
+C_PROBE = r"""
+#include <stdio.h>
+#include <stddef.h>
+#include "kvb.h"
+int main(void)
+{
+    printf("%zu %zu %zu %zu\n", sizeof(kvb_shape), offsetof(kvb_shape, out_dtype), offsetof(kvb_shape, rec_dtype),
+           offsetof(kvb_shape, scale));
+    printf("%zu %zu %zu %zu %zu %zu %zu\n", sizeof(kvb_store), offsetof(kvb_store, buf_u), offsetof(kvb_store, fill),
+           offsetof(kvb_store, n_slots), offsetof(kvb_store, flags), offsetof(kvb_store, block_table),
+           offsetof(kvb_store, n_blocks));
+    printf("%d %d %d %d %d %d\n", KVB_VERSION, KVB_F32, KVB_BF16, KVB_F16, KVB_STORE_STREAM, KVB_STORE_RESIDENT);
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
+    """include/kvb.h compiles as strict C99 (it is the boundary: no C++ in it), and the struct
+    layout a C caller sees is the one the ctypes binding marshals."""
+    src = tmp_path / "probe.c"
+    src.write_text(C_PROBE)
+    exe = tmp_path / "probe"
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    lines = subprocess.check_output([str(exe)], text=True).splitlines()
+    sh = [int(x) for x in lines[0].split()]
+    st = [int(x) for x in lines[1].split()]
+    co = [int(x) for x in lines[2].split()]
+    assert sh == [ctypes.sizeof(kvb.KvbShape), kvb.KvbShape.out_dtype.offset, kvb.KvbShape.rec_dtype.offset,
+                  kvb.KvbShape.scale.offset]
+    assert st == [ctypes.sizeof(kvb.KvbStore), kvb.KvbStore.buf_u.offset, kvb.KvbStore.fill.offset,
+                  kvb.KvbStore.n_slots.offset, kvb.KvbStore.flags.offset, kvb.KvbStore.block_table.offset,
+                  kvb.KvbStore.n_blocks.offset]
+    assert co == [kvb.version(), kvb.F32, kvb.BF16, kvb.F16, kvb.STORE_STREAM, kvb.STORE_RESIDENT]
