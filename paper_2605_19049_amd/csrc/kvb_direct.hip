@@ -299,11 +299,15 @@ __device__ __forceinline__ f32x4_t mm16_pieces(const uint2 (&x)[NPX], const uint
 //
 // LDS, one region X used three times -- the staged keys; then the fp32 tiles N_de (d > e), T_d,
 // A_32, W_20, W_21; then the pieces of A^ -- and the pieces of M next to it: 36 KB for bf16,
-// four workgroups per CU.  A wave owns 32 dv columns: column tile c of wave w holds columns
+// four workgroups per CU (28 KB and five for fp16).  A wave owns 32 dv columns: column tile c of wave w holds columns
 // 32 w + 2 n + c (n = 0..15), so a lane's two tiles are adjacent columns.
 // ---------------------------------------------------------------------------
+// Workgroups per CU: the two fp16 pieces need 28 KB of LDS and 92 registers, which leaves room for
+// five (6 % faster than four on ragged lengths); the three bf16 pieces need 36 KB and 124.
+template <typename T>
+constexpr int DIRECT_WG_PER_CU = __is_same(T, f16_t) ? 5 : 4;
 template <typename TIn, typename TRec, bool PAGED>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4, 4))) void kvb_direct_mfma_kernel(
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(DIRECT_WG_PER_CU<TIn>, DIRECT_WG_PER_CU<TIn>))) void kvb_direct_mfma_kernel(
     const int32_t *len_arg, int32_t Hv_arg, int32_t nblocks_arg, const DirectArgs a)
 {
     // The three leading arguments repeat a.len, a.Hv and the grid size: as plain leading kernel arguments
