@@ -1,12 +1,18 @@
 // kvb -- KVBuffer-style Gated DeltaNet decoding, HIP kernels for gfx950 behind the C ABI of
 // include/kvb.h.  This header holds what the translation units share: device helpers, the
 // argument structs of the kernels, and the launch plumbing.
-//   kvb_step_kernel.h, kvb_step_bf16.hip, kvb_step_f32.hip
-//                   kvb_step_kernel (decode and the vector-ALU verify), one unit per input type
-//   kvb_verify.hip  kvb_verify_mfma_kernel
-//   kvb_flush.hip   kvb_flush_kernel, kvb_compact_kernel
-//   kvb_direct.hip  kvb_direct_mfma_kernel, kvb_direct_kernel
-//   kvb_api.hip     argument checks, the extern "C" entry points, the kernel timer
+//   kvb_step_kernel.h    kvb_step_kernel (decode and the vector-ALU verify); instantiated per
+//                        (input type, record type) by kvb_step_f32.hip, kvb_step_bf16.hip,
+//                        kvb_step_bf16_r16.hip, kvb_step_f16.hip, kvb_step_f16_r16.hip
+//   kvb_verify_kernel.h  kvb_verify_mfma_kernel; instantiated by kvb_verify_bf16.hip, kvb_verify_f16.hip
+//   kvb_flush.hip        kvb_flush_mfma_kernel, kvb_flush_kernel, kvb_compact_kernel
+//   kvb_direct.hip       kvb_direct_mfma_kernel, kvb_direct_mfma_long_kernel, kvb_direct_kernel
+//   kvb_api.hip          argument checks, the extern "C" entry points, the kernel timer
+//
+// Element types (Sec. 4.1: 16-bit vectors and records beside a fp32 state): TIn is the type of
+// q, k, v and of the buffered keys (float, bf16_t or f16_t), TRec that of the buffered delta
+// values (float, or TIn when that is 16-bit); outputs are fp32 or TIn, chosen at run time at the
+// final store.  All arithmetic is fp32.
 //
 // Work decomposition (every kernel): one 256-thread workgroup per (request b,
 // v-head h); the committed state S0[dk][dv] (fp32, dv contiguous, 64 KB at
@@ -15,9 +21,11 @@
 // App. A.1, the paragraph after Eq. 16), a few KB.
 //   kvb_step_kernel         decode (T = 1) and generic verify: vector ALUs; a thread owns
 //                           4 adjacent dv columns of 16 state rows (16-byte loads)
-//   kvb_verify_mfma_kernel  verify, bf16 / d = 128: matrix cores; a wave owns 32 dv columns
-//   kvb_flush_kernel        deferred state update as its own launch
-//   kvb_direct_mfma_kernel  short contexts, bf16 / d = 128: matrix cores throughout
+//   kvb_verify_mfma_kernel  verify, 16-bit inputs / d = 128: matrix cores; a wave owns 32 dv columns
+//   kvb_flush_mfma_kernel   deferred state update, 16-bit inputs / d = 128: matrix cores on exact
+//                           16-bit pieces of the fp32 factor
+//   kvb_flush_kernel        the same for the other types and head sizes: vector ALUs
+//   kvb_direct_mfma_kernel  short contexts, 16-bit inputs / d = 128: matrix cores throughout
 //   kvb_direct_kernel       short contexts, other types and head sizes
 //
 // Notation follows App. A.1: gamma_i = exp(G_i), Gamma_il = exp(G_i - G_l).

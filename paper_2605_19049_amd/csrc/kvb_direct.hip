@@ -114,15 +114,17 @@ __global__ __launch_bounds__(NT) void kvb_direct_kernel(const DirectArgs a)
 
 // ---------------------------------------------------------------------------
 // kvb_direct for 16-bit inputs (bf16 or fp16) and d = 128, on the matrix cores throughout.
+// What the two kernels below share.
 //
 // The context is cut into blocks of 16 rows.  With N_il = beta_i Gamma_il (k_i.k_l) (l < i)
 // and M_il = Gamma_il (q_i.k_l) (l <= i) the parallel form (Eq. 13) is
-//     (I + N) U = Diag(beta) V,      O = M U,
-// solved block row by block row:  U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),
+//     (I + N) U = Diag(beta) V,      O = M U.
+// The kernel for up to 128 tokens solves it block row by block row,
+//     U_d = T_d ( beta V_d - sum_{e<d} N_de U_e ),      O_d = sum_{e<=d} M_de U_e,
 // T_d = (I + N_dd)^-1 by blocked inversion (unit_lower_inverse16 below; N_dd is strictly lower),
-// O_d = sum_{e<=d} M_de U_e.
+// with fp32 operands on v_mfma_f32_16x16x4_f32 (exact products) after the Gram tiles; the
+// kernel for up to 64 tokens forms the whole inverse and multiplies (see its own header).
 //   * Gram tiles (k.k, q.k over dk = 128, 16-bit operands): v_mfma_f32_16x16x32_{bf16,f16}.
-//   * everything after that has fp32 operands: v_mfma_f32_16x16x4_f32 (exact products).
 //
 // Register chaining.  Call "A-form" of a 16x16 matrix X the register layout in which lane l
 // holds X[l%16][4*(l/16)+v], v = 0..3, and "B-form" the one with X[4*(l/16)+v][l%16].  An
@@ -682,8 +684,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(DIRECT_WG_PE
 }
 
 // ---------------------------------------------------------------------------
-// kvb_direct for contexts of 65 .. 128 tokens (bf16, d = 128): the same method with 8 blocks of 16
-// rows.  Kept apart from the kernel above, which is tuned around "4 blocks, one per wave" (its raw
+// kvb_direct for contexts of 65 .. 128 tokens (16-bit inputs, d = 128): the block-row method with 8
+// blocks of 16 rows.  Kept apart from the kernel above, which is tuned around "4 blocks, one per wave" (its raw
 // Gram tiles and query operands all fit in registers at once).  Here a wave owns two diagonal
 // blocks and 16 of the 64 off-diagonal k.k and q.k tiles; the query rows of a tile are fetched
 // one tile ahead; the tile region (80 tiles, 80 KB) again takes the place of the staged keys.
