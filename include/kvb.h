@@ -68,8 +68,8 @@ extern "C" {
 
 /* kvb_store.flags: how the state should travel through the caches.  With neither bit the
  * library streams (non-temporal loads, and non-temporal stores when the state is written
- * back) when the states one call touches, 4 * B * Hv * dk * dv bytes, exceed 384 MiB: one and
- * a half times the 256 MB last-level cache, because a state of 256 MiB that is re-read every
+ * back) when the states one call touches, 4 * B * Hv * dk * dv bytes, exceed 288 MiB: a little
+ * more than the 256 MB last-level cache, because a state of 256 MiB that is re-read every
  * step still finds most of itself there; kvb_flush, which passes the state through the cache
  * in both directions, switches at 192 MiB.  A model with many GDN layers should set
  * KVB_STORE_STREAM: each layer's state is next read one token later, after every other

@@ -66,13 +66,14 @@ int check_tokens(const void *q, const void *k, const void *v, const float *g, co
 }
 
 // Whether the state should be streamed past the caches: the caller's hint, else by this
-// call's own state footprint against the 256 MB last-level cache.  For the calls that only read
-// the state the switch sits at 1.5 times the cache: a state of 256 MiB re-read every step still
-// finds most of itself there and runs faster with plain loads, one of 512 MiB does not.  kvb_flush
+// call's own state footprint against the 256 MB last-level cache.  For decoding and verification
+// the switch sits at 288 MiB: a state of 256 MiB re-read every step still finds most of itself
+// in the cache and runs faster with plain loads (kvb_decode_flush at C = 16: 49 against 53 us per
+// step), at 288 MiB the two are level (59 us), at 320 MiB streaming wins (65 against 71).  kvb_flush
 // reads and writes the state, twice the lines through the cache: measured, streaming wins from
 // about 200 MiB of state on (16 records: 65 against 71 us at 192 MiB, 88 against 84 at 224 MiB;
 // 64 records: 139 against 107 us at 256 MiB), so its switch sits at 192 MiB.
-bool stream_state(const kvb_shape *sh, const kvb_store *st, double limit_mib = 384.0)
+bool stream_state(const kvb_shape *sh, const kvb_store *st, double limit_mib = 288.0)
 {
     if (st->flags & KVB_STORE_STREAM)
         return true;
