@@ -801,9 +801,10 @@ def test_kv_only_verify_and_stream_hint_do_not_change_results():
         assert torch.equal(x, y)
 
 
-@pytest.mark.parametrize("in_dtype, rec_dtype, cap", [("bf16", "f32", 8), ("bf16", "f32", 40), ("f16", "f16", 40),
-                                                      ("bf16", "bf16", 16), ("f32", "f32", 12)])
-def test_stream_hint_does_not_change_kvb_flush(in_dtype, rec_dtype, cap):
+@pytest.mark.parametrize("in_dtype, rec_dtype, cap, block_size", [
+    ("bf16", "f32", 8, None), ("bf16", "f32", 40, None), ("f16", "f16", 40, None), ("bf16", "bf16", 16, None),
+    ("f32", "f32", 12, None), ("bf16", "f32", 16, 8), ("f16", "f32", 48, 16)])
+def test_stream_hint_does_not_change_kvb_flush(in_dtype, rec_dtype, cap, block_size):
     """kvb_flush with the state streamed past the caches (non-temporal loads and stores, what the
     library chooses by itself for large batches) against the default path, bit for bit."""
     rng = np.random.default_rng(1200 + cap)
@@ -812,7 +813,7 @@ def test_stream_hint_does_not_change_kvb_flush(in_dtype, rec_dtype, cap):
     tok = H.upload_tokens(synth.token_stream(rng, B, cap, Hk, Hv, d, d, in_dtype), in_dtype)
     res = []
     for flags in (kvb.STORE_RESIDENT, kvb.STORE_STREAM):
-        lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, rec_dtype=rec_dtype)
+        lay = H.Layer(B, Hk, Hv, d, d, cap=cap, in_dtype=in_dtype, rec_dtype=rec_dtype, block_size=block_size)
         lay.set_state(S0)
         out = lay.new_out(B, Hv, d)
         for t in range(cap - 1):
